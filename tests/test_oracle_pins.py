@@ -1,0 +1,354 @@
+"""Pins for the CPU oracle: facts fixed by the paper's definitions and by mathematics.
+
+None of these retype the oracle's own formulae; each checks the oracle against a
+closed form, a hand-derived example, an invariant, a special case that reduces to
+something simpler, or an independently written brute force.
+"""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def random_layer(seed, T=7, E=5, H=4, F=6):
+    g = rng(seed)
+    return (g.standard_normal((T, H)), g.standard_normal((E, H)),
+            g.standard_normal((E, F, H)), g.standard_normal((E, F, H)),
+            g.standard_normal((E, H, F)))
+
+
+# ----------------------------------------------------------------------------- O1
+def test_expert_scalar_closed_form():
+    # H = F = 1: gate = ln 3 -> sigmoid = 3/4; up = 2 ln 3; Y = 5 * (3/4 ln 3) * (2 ln 3)
+    x = np.array([[math.log(3.0)]])
+    logits, Y = oracle.expert_outputs(x, np.array([[7.0]]), np.array([[[1.0]]]),
+                                      np.array([[[2.0]]]), np.array([[[5.0]]]))
+    assert Y.shape == (1, 1, 1)
+    assert Y[0, 0, 0] == pytest.approx(7.5 * math.log(3.0) ** 2, rel=1e-14)
+    assert logits[0, 0] == pytest.approx(7.0 * math.log(3.0), rel=1e-14)
+
+
+def test_expert_one_hot_indexing():
+    # A single non-zero entry in each operand: catches any transposed or mis-indexed operand.
+    T, E, H, F = 3, 2, 4, 5
+    x = np.zeros((T, H)); x[1, 2] = 2.0
+    Wg = np.zeros((E, H)); Wg[1, 2] = 3.0
+    W1 = np.zeros((E, F, H)); W3 = np.zeros((E, F, H)); W2 = np.zeros((E, H, F))
+    W1[1, 4, 2] = 0.5      # gate pre-activation 1.0 at f = 4
+    W3[1, 4, 2] = -1.5     # up value -3.0
+    W2[1, 3, 4] = 2.0      # lands in hidden unit 3
+    logits, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    want = (1.0 / (1.0 + math.exp(-1.0))) * (-3.0) * 2.0
+    expect = np.zeros((E, T, H)); expect[1, 1, 3] = want
+    np.testing.assert_allclose(Y, expect, rtol=1e-14, atol=0)
+    el = np.zeros((T, E)); el[1, 1] = 6.0
+    np.testing.assert_array_equal(logits, el)
+
+
+def test_expert_zero_branches_and_linearity():
+    x, Wg, W1, W3, W2 = random_layer(1)
+    _, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    _, Y0 = oracle.expert_outputs(x, Wg, W1, np.zeros_like(W3), W2)
+    assert np.all(Y0 == 0.0)                                   # linear branch zero
+    _, Yg = oracle.expert_outputs(x, Wg, np.zeros_like(W1), W3, W2)
+    assert np.all(Yg == 0.0)                                   # silu(0) = 0
+    _, Y2 = oracle.expert_outputs(x, Wg, W1, W3, 2.5 * W2)     # linear in W2
+    np.testing.assert_allclose(Y2, 2.5 * Y, rtol=1e-13)
+    _, Y3 = oracle.expert_outputs(x, Wg, W1, -W3, W2)          # odd in W3
+    np.testing.assert_allclose(Y3, -Y, rtol=1e-13)
+    # silu is not odd: silu(a) - silu(-a) = a  =>  Y(W1) - Y(-W1) = (x W1^T * x W3^T) W2^T
+    _, Ym = oracle.expert_outputs(x, Wg, -W1, W3, W2)
+    for e in range(len(W1)):
+        lin = ((x @ W1[e].T) * (x @ W3[e].T)) @ W2[e].T
+        np.testing.assert_allclose(Y[e] - Ym[e], lin, rtol=1e-11, atol=1e-11)
+
+
+def test_silu_large_arguments():
+    assert oracle.silu(np.array([50.0]))[0] == pytest.approx(50.0, rel=1e-15)
+    assert abs(oracle.silu(np.array([-50.0]))[0]) < 1e-19
+    assert oracle.silu(np.array([0.0]))[0] == 0.0
+
+
+# ------------------------------------------------------------------------- Eq. 1
+def test_routing_order_ties_go_to_lower_index():
+    logits = np.array([[0.5, 2.0, 2.0, -1.0, 2.0], [1.0, 1.0, 1.0, 1.0, 1.0]])
+    order = oracle.routing_order(logits)
+    assert order[0].tolist() == [1, 2, 4, 0, 3]
+    assert order[1].tolist() == [0, 1, 2, 3, 4]
+
+
+def test_eq1_weights_sum_to_one_and_match_full_softmax():
+    g = rng(2)
+    logits = g.standard_normal((50, 8)) * 3.0
+    order = oracle.routing_order(logits)
+    k = 3
+    sel = np.zeros_like(logits, dtype=bool)
+    np.put_along_axis(sel, order[:, :k], True, axis=1)
+    w = oracle.renormalised_weights(logits, sel)
+    np.testing.assert_allclose(w.sum(1), 1.0, rtol=0, atol=1e-15)
+    assert np.all(w[~sel] == 0.0)
+    # The paper's route: softmax over ALL n logits, keep the top-k, divide by their sum.
+    full = np.exp(logits) / np.exp(logits).sum(1, keepdims=True)
+    topk = np.where(sel, full, 0.0)
+    np.testing.assert_allclose(w, topk / topk.sum(1, keepdims=True), rtol=1e-12, atol=0)
+    # shift invariance
+    w2 = oracle.renormalised_weights(logits + 123.25, sel)
+    np.testing.assert_allclose(w2, w, rtol=1e-12)
+
+
+def test_layer_output_two_experts_closed_form():
+    # weights (2/3, 1/3) from logits (ln 4, ln 2, ln 1), see tests/golden/hand_example_eq3.txt
+    logits = np.log(np.array([[4.0, 2.0, 1.0]]))
+    Y = np.array([[[1.0, 0.0]], [[0.0, 1.0]], [[1.0, 1.0]]])
+    z = oracle.layer_output(logits, Y, 2)
+    np.testing.assert_allclose(z, [[2.0 / 3.0, 1.0 / 3.0]], rtol=1e-15)
+
+
+# ------------------------------------------------------------------ subset index
+@pytest.mark.parametrize("E,r", [(4, 2), (8, 6), (8, 4), (16, 8), (16, 12), (5, 5), (6, 1)])
+def test_subsets_each_once_in_lexicographic_order(E, r):
+    subs = oracle.kept_subsets(E, r)
+    assert len(subs) == math.comb(E, r) == math.comb(E, E - r)
+    assert len(set(subs)) == len(subs)
+    assert all(len(s) == r and list(s) == sorted(set(s)) for s in subs)
+    assert all(a < b for a, b in zip(subs, subs[1:]))          # strictly increasing tuples
+    assert subs[0] == tuple(range(r))
+    masks = [oracle.subset_mask(s) for s in subs]
+    assert all(bin(m).count("1") == r for m in masks)
+    assert all(m < (1 << E) for m in masks)
+
+
+# ------------------------------------------------------------------------- Eq. 3
+def test_hand_example_golden():
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "hand_example_eq3.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    logits = np.log(np.array([[4.0, 2.0, 1.0]]))
+    Y = np.array([[[1.0, 0.0]], [[0.0, 1.0]], [[1.0, 1.0]]])
+    loss, amin, masks = oracle.prune_enumerate(logits, Y, k=2, r=2)
+    assert len(rows) == len(loss) == 3
+    for idx, mask, num, den in rows:
+        assert masks[int(idx)] == int(mask)
+        assert loss[int(idx)] == pytest.approx(float(Fraction(int(num), int(den))), rel=1e-14, abs=1e-300)
+    assert amin == 0 and loss[0] == 0.0
+    z_kept02 = oracle.pruned_layer_output(logits, Y, (0, 2), 2)
+    np.testing.assert_allclose(z_kept02, [[1.0, 0.2]], rtol=1e-15)
+
+
+def enumeration_case(seed, T=40, E=6, H=5):
+    g = rng(seed)
+    return g.standard_normal((T, E)), g.standard_normal((E, T, H))
+
+
+def test_keep_all_experts_gives_exactly_zero():
+    logits, Y = enumeration_case(3)
+    for k in (1, 2, 3):
+        loss, amin, masks = oracle.prune_enumerate(logits, Y, k, r=6)
+        assert loss.tolist() == [0.0] and amin == 0 and masks.tolist() == [63]
+
+
+@pytest.mark.parametrize("E,k,r,T", [(4, 2, 2, 64), (8, 2, 6, 33), (6, 3, 4, 50)])
+def test_unaffected_pairs_are_exactly_zero_and_counted(E, k, r, T):
+    # A token whose full top-k all survive in C contributes exactly 0; with generic
+    # (tie-free) inputs those are the only zero pairs: T * C(E-k, r-k) of them.
+    g = rng(4)
+    logits, Y = g.standard_normal((T, E)), g.standard_normal((E, T, 3))
+    subs = oracle.kept_subsets(E, r)
+    zero_pairs = 0
+    for t in range(T):
+        lt, Yt = logits[t:t + 1], Y[:, t:t + 1, :]
+        loss_t, _, _ = oracle.prune_enumerate(lt, Yt, k, r)
+        top = set(np.argsort(-lt[0], kind="stable")[:k].tolist())
+        for i, c in enumerate(subs):
+            if top <= set(c):
+                assert loss_t[i] == 0.0
+            else:
+                assert loss_t[i] > 0.0
+        zero_pairs += int(np.sum(loss_t == 0.0))
+    assert zero_pairs == T * math.comb(E - k, r - k)
+
+
+def test_top1_special_case():
+    # k = 1: the layer output is the arg-max expert's output; the pruned layer's is the
+    # arg-max expert among the kept ones.
+    logits, Y = enumeration_case(5, T=30, E=5, H=4)
+    loss, _, _ = oracle.prune_enumerate(logits, Y, k=1, r=3)
+    for i, c in enumerate(itertools.combinations(range(5), 3)):
+        want = 0.0
+        for t in range(30):
+            e_full = int(np.argmax(logits[t]))
+            e_kept = max(c, key=lambda e: logits[t, e])
+            want += float(np.sum((Y[e_kept, t] - Y[e_full, t]) ** 2))
+        assert loss[i] == pytest.approx(want, rel=1e-12, abs=1e-300)
+
+
+def test_scale_law_shift_invariance_and_token_additivity():
+    logits, Y = enumeration_case(6)
+    loss, _, _ = oracle.prune_enumerate(logits, Y, 2, 4)
+    loss_scaled, _, _ = oracle.prune_enumerate(logits, -3.0 * Y, 2, 4)
+    np.testing.assert_allclose(loss_scaled, 9.0 * loss, rtol=1e-12)
+    loss_shift, _, _ = oracle.prune_enumerate(logits + 2.0, Y, 2, 4)   # exact in binary for +2
+    np.testing.assert_allclose(loss_shift, loss, rtol=1e-10)
+    la, _, _ = oracle.prune_enumerate(logits[:17], Y[:, :17], 2, 4)
+    lb, _, _ = oracle.prune_enumerate(logits[17:], Y[:, 17:], 2, 4)
+    np.testing.assert_allclose(la + lb, loss, rtol=1e-12)
+    ls, amin, _ = oracle.prune_enumerate_streamed(logits, Y, 2, 4, chunk=9)
+    np.testing.assert_allclose(ls, loss, rtol=1e-12)
+    assert amin == int(np.argmin(loss))
+
+
+def test_expert_relabelling_permutes_subsets():
+    logits, Y = enumeration_case(7, E=6)
+    perm = rng(70).permutation(6)                 # new label p -> old expert perm[p]
+    loss, _, _ = oracle.prune_enumerate(logits, Y, 2, 4)
+    loss_p, _, _ = oracle.prune_enumerate(logits[:, perm], Y[perm], 2, 4)
+    subs = oracle.kept_subsets(6, 4)
+    index = {s: i for i, s in enumerate(subs)}
+    for j, kept_new in enumerate(subs):
+        kept_old = tuple(sorted(int(perm[p]) for p in kept_new))
+        assert loss_p[j] == pytest.approx(loss[index[kept_old]], rel=1e-9)
+    np.testing.assert_allclose(np.sort(loss_p), np.sort(loss), rtol=1e-9)
+
+
+def test_quadratic_form_identity():
+    # ||sum_e d_e Y_e||^2 = d^T (Y_t Y_t^T) d with d = pruned weights - full weights: the
+    # identity the GPU path relies on, evaluated here with independently built d.
+    logits, Y = enumeration_case(8, T=25, E=6, H=7)
+    k, r = 2, 3
+    loss, _, _ = oracle.prune_enumerate(logits, Y, k, r)
+    for i, c in enumerate(itertools.combinations(range(6), r)):
+        total = 0.0
+        for t in range(25):
+            l = logits[t]
+            full = sorted(range(6), key=lambda e: (-l[e], e))[:k]
+            kept = sorted(c, key=lambda e: (-l[e], e))[:k]
+            d = np.zeros(6)
+            d[kept] += np.exp(l[kept]) / np.exp(l[kept]).sum()
+            d[full] -= np.exp(l[full]) / np.exp(l[full]).sum()
+            G = Y[:, t, :] @ Y[:, t, :].T
+            total += d @ G @ d
+        assert loss[i] == pytest.approx(total, rel=1e-10)
+
+
+def test_planted_argmin():
+    # Experts 1 and 4 get logits of -1e9 on every token: they are never routed to, so the
+    # subset that drops exactly those two reproduces the layer and is the argmin with loss 0.
+    logits, Y = enumeration_case(9, T=64, E=6, H=4)
+    logits[:, [1, 4]] = -1e9
+    loss, amin, masks = oracle.prune_enumerate(logits, Y, 2, 4)
+    want = oracle.kept_subsets(6, 4).index((0, 2, 3, 5))
+    assert amin == want and loss[want] == 0.0
+    assert masks[want] == 0b101101
+    assert np.all(np.delete(loss, want) > 0.0)
+    # Both survivors of a subset at -1e9: Eq. 1 must still give finite (1/2, 1/2) weights.
+    l2, _, _ = oracle.prune_enumerate(logits, Y, 2, 2)
+    assert np.all(np.isfinite(l2))
+    i14 = oracle.kept_subsets(6, 2).index((1, 4))
+    z = oracle.pruned_layer_output(logits, Y, (1, 4), 2)
+    np.testing.assert_allclose(z, 0.5 * (Y[1] + Y[4]), rtol=1e-14)
+    assert l2[i14] > 0.0
+
+
+def test_r_smaller_than_k_uses_all_kept():
+    logits, Y = enumeration_case(10, T=12, E=4, H=3)
+    loss, _, _ = oracle.prune_enumerate(logits, Y, k=3, r=1)
+    full = oracle.layer_output(logits, Y, 3)
+    for e in range(4):
+        assert loss[e] == pytest.approx(float(np.sum((Y[e] - full) ** 2)), rel=1e-12)
+
+
+@pytest.mark.parametrize("E,k,r", [(3, 2, 2), (4, 2, 2), (5, 2, 3), (5, 3, 4), (4, 1, 2), (5, 4, 2)])
+def test_against_pure_python_brute_force(E, k, r):
+    g = rng(100 + 10 * E + r)
+    T, H = 6, 3
+    logits = g.standard_normal((T, E))
+    logits[2, 0] = logits[2, E - 1]            # an exact tie inside one token
+    Y = g.standard_normal((E, T, H))
+    loss, amin, masks = oracle.prune_enumerate(logits, Y, k, r)
+    bf, kept_sets = oracle.brute_force_enumerate(logits.tolist(), Y.tolist(), k, r)
+    np.testing.assert_allclose(loss, bf, rtol=1e-11, atol=1e-14)
+    assert kept_sets == oracle.kept_subsets(E, r)
+    assert [oracle.subset_mask(c) for c in kept_sets] == masks.tolist()
+    assert amin == min(range(len(bf)), key=lambda i: (loss[i], i))
+
+
+# ---------------------------------------------------------------- Sec. 3.3 / A.2
+def skip_case(seed, T=60, E=5, H=6, F=8):
+    return random_layer(seed, T=T, E=E, H=H, F=F)
+
+
+def test_skip_beta_zero_is_eq2_and_beta_large_is_top1():
+    x, Wg, W1, W3, W2 = skip_case(11)
+    logits, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    out0, skip0, e0, e1 = oracle.forward_skip(x, Wg, W1, W3, W2, beta=0.0)
+    assert not skip0.any()
+    np.testing.assert_allclose(out0, oracle.layer_output(logits, Y, 2), rtol=1e-11, atol=1e-13)
+    out1, skip1, e0b, _ = oracle.forward_skip(x, Wg, W1, W3, W2, beta=1.5)
+    assert skip1.all()
+    t = np.arange(x.shape[0])
+    np.testing.assert_allclose(out1, Y[e0b, t], rtol=1e-11, atol=1e-13)
+    assert np.array_equal(e0, np.argmax(logits, 1))
+    assert np.all(logits[t, e0] >= logits[t, e1])
+
+
+def test_skip_error_closed_form_and_bound():
+    # App. A.2 with k = 2, i = 1: z_hat - z = w~_e1 (f_e0 - f_e1), so the error norm is
+    # w~_e1 ||f_e0 - f_e1|| exactly, and <= (w_e1 / (w_e0 + w_e1)) D for any D >= the distance.
+    x, Wg, W1, W3, W2 = skip_case(12)
+    logits, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    beta = 0.6
+    out_s, skip, e0, e1 = oracle.forward_skip(x, Wg, W1, W3, W2, beta)
+    out_f, _, _, _ = oracle.forward_skip(x, Wg, W1, W3, W2, 0.0)
+    assert 0 < skip.sum() < len(skip)
+    t = np.arange(x.shape[0])
+    w = np.exp(logits) / np.exp(logits).sum(1, keepdims=True)      # full softmax, as in the paper
+    w0, w1 = w[t, e0], w[t, e1]
+    assert np.array_equal(skip, w1 < beta * w0)                      # the rule as printed (no near-ties here)
+    dist = np.linalg.norm(Y[e0, t] - Y[e1, t], axis=1)
+    err = np.linalg.norm(out_s - out_f, axis=1)
+    np.testing.assert_allclose(err[skip], (w1 / (w0 + w1) * dist)[skip], rtol=1e-10)
+    assert np.all(err[~skip] == 0.0)
+    D = dist.max()
+    assert np.all(err <= w1 / (w0 + w1) * D * (1 + 1e-12))
+
+
+def test_skip_set_monotone_in_beta_and_median_halves():
+    g = rng(13)
+    logits = g.standard_normal((1000, 8)).astype(np.float32)
+    prev = None
+    for beta in (0.0, 0.1, 0.3, 0.5, 0.7, 0.9, 1.0, 1.1):
+        _, _, skip, delta = oracle.skip_decision(logits, beta)
+        assert np.all(delta <= 0)
+        if prev is not None:
+            assert np.all(skip | ~prev)          # once skipped, skipped for any larger beta
+        prev = skip
+    assert prev.all()
+    beta = oracle.median_skip_ratio(logits)
+    _, _, skip, _ = oracle.skip_decision(logits, beta)
+    assert abs(skip.mean() - 0.5) <= 1.0 / len(logits) + 1e-12
+    # median convention: mean of the two middle order statistics
+    l = np.asarray(logits, dtype=np.float64)
+    srt = np.sort(l, axis=1)
+    rho = np.sort(np.exp(srt[:, -2] - srt[:, -1]))
+    assert beta == pytest.approx(0.5 * (rho[499] + rho[500]), rel=1e-15)
+
+
+def test_skip_uses_given_logits():
+    x, Wg, W1, W3, W2 = skip_case(14, T=20)
+    forced = np.zeros((20, 5), dtype=np.float32)
+    forced[:, 3] = 2.0
+    forced[:, 1] = 1.0
+    out, skip, e0, e1 = oracle.forward_skip(x, Wg, W1, W3, W2, beta=0.5, logits=forced)
+    assert np.all(e0 == 3) and np.all(e1 == 1)
+    assert skip.all()                      # exp(-1) = 0.37 < 0.5
+    np.testing.assert_allclose(out, oracle.expert_ffn(x, W1[3], W3[3], W2[3]), rtol=1e-12)
