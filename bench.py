@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the expert-pruning hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic batch of the Mixtral-shaped
+layer (E=8, top-2, H=4096, F=14336):
+    moe_expert_outputs on T=262144 calibration tokens            (router + expert GEMMs)
+    prune_enumerate for r=6 (28 subsets) and r=4 (70 subsets)    (Gram + scoring + argmin)
+    moe_forward_skip on the first 32768 tokens, beta = median    (dynamic skipping forward)
+Inputs are generated on the device before the timed region.  `value` is
+(28 + 70) * T subset-token pairs per second of whole-step time.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the gate/up GEMM), timed per
+launch with HIP events on the launch stream inside the timed steps; `kernels` carries the same
+figures for every kernel; `cpu_baseline` times the fp64 numpy oracle on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0     # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {"C3": None, "C2": None}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3"],
+                    help="C3 = Mixtral-shaped layer (the headline); C2 = mid layer (quick check)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, layer, Y, logits, torch, wl):
+    """The oracle as it stands, on a bounded sample of the same workload (host cores)."""
+    import numpy as np
+
+    import oracle
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n1 = 128 if cfg.H >= 4096 else 512          # tokens through all E experts (fp64 GEMMs)
+    n2 = 2048 if cfg.H >= 4096 else 4096        # tokens through the enumeration, all r
+    x = wl.to_f64(layer["x"][:n1])
+    Wg = wl.to_f64(layer["Wgate"])
+    t_o1 = 0.0
+    for e in range(cfg.E):                       # one expert at a time: fp64 weights are large
+        W1, W3, W2 = (wl.to_f64(layer[n][e:e + 1]) for n in ("W1", "W3", "W2"))
+        t0 = time.perf_counter()
+        oracle.expert_outputs(x, Wg, W1, W3, W2)
+        t_o1 += time.perf_counter() - t0
+    l64, Y64 = wl.to_f64(logits[:n2]), wl.to_f64(Y[:, :n2])
+    t0 = time.perf_counter()
+    for r in cfg.rs:
+        oracle.prune_enumerate(l64, Y64, cfg.k, r)
+    t_o2 = time.perf_counter() - t0
+    n_sub = sum(math.comb(cfg.E, r) for r in cfg.rs)
+    per_token = t_o1 / n1 + t_o2 / n2
+    return {
+        "value": n_sub / per_token, "unit": "subset·tokens/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"expert_outputs on {n1} tokens x {cfg.E} experts ({t_o1:.2f} s) + prune_enumerate "
+                  f"r={list(cfg.rs)} on {n2} tokens ({t_o2:.2f} s), scaled per token",
+        "expert_outputs_tokens_per_s": n1 / t_o1, "enumerate_subset_tokens_per_s": n_sub * n2 / t_o2,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus N with N > 1 is not supported "
+              "(the path shards over tokens with one small all-reduce, see DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2402_14800_amd as pkg
+    from paper_2402_14800_amd import binding
+    from paper_2402_14800_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.workload]
+    T_skip = min(32768, cfg.T)
+    layer = wl.make_layer(cfg, device=dev)            # torch generator on the device
+    x, Wg, W1, W3, W2 = (layer[n] for n in ("x", "Wgate", "W1", "W3", "W2"))
+    E, H, F, T, k = cfg.E, cfg.H, cfg.F, cfg.T, cfg.k
+    dt = binding.MOEP_BF16
+
+    # All buffers are allocated once, outside the timed region.
+    logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+    Y = torch.empty((E, T, H), dtype=torch.bfloat16, device=dev)
+    ws_exp = torch.empty(binding.moe_expert_outputs_workspace(T, E, H, F, dt), dtype=torch.uint8, device=dev)
+    ws_enum = torch.empty(max(binding.prune_enumerate_workspace(T, E, H, k, r, dt) for r in cfg.rs),
+                          dtype=torch.uint8, device=dev)
+    ws_skip = torch.empty(binding.moe_forward_skip_workspace(T_skip, E, H, F, dt), dtype=torch.uint8, device=dev)
+    x_skip = x[:T_skip]
+
+    # beta = median of w_e1 / w_e0 over the skip batch (Sec. 3.3), from a router pass done up front.
+    _, _, lg, _ = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip)
+    top = torch.topk(lg.double(), 2, dim=1).values
+    beta = float(torch.exp(top[:, 1] - top[:, 0]).median().item()) if T_skip % 2 else \
+        float(torch.exp(top[:, 1] - top[:, 0]).sort().values[T_skip // 2 - 1:T_skip // 2 + 1].mean().item())
+    del lg, top
+
+    results = {}
+
+    def step():
+        pkg.moe_expert_outputs(x, Wg, W1, W3, W2, logits=logits, Y=Y, workspace=ws_exp)
+        for r in cfg.rs:
+            results[r] = pkg.prune_enumerate(logits, Y, k, r, workspace=ws_enum)
+        results["skip"] = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, beta, workspace=ws_skip,
+                                               want_logits=False, want_top2=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    pkg.kernel_timing_enable(True)
+    pkg.kernel_timing_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    timing = pkg.kernel_timing_collect()
+    pkg.kernel_timing_enable(False)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    n_sub = sum(math.comb(E, r) for r in cfg.rs)
+    value = n_sub * T / (elapsed / args.steps)
+
+    # ---- per-kernel figures: algorithmic work per launch / measured launch time ----
+    es = 2
+    slots = float(2 * T_skip - int(results["skip"][1].sum().item()))
+    work = {   # kernel -> (bound, algorithmic flops or bytes per launch)
+        "gemm_gate_up_swiglu": ("mfma", 4.0 * T * H * F),
+        "gemm_down": ("mfma", 2.0 * T * H * F),
+        "gemm_gate_up_swiglu_routed": ("mfma", 4.0 * slots * H * F),
+        "gemm_down_routed": ("mfma", 2.0 * slots * H * F),
+        "gram": ("hbm", float(E) * T * H * es + 4.0 * T * E * E),
+        "router_logits": ("hbm", None),      # launched with two different T: reported as time only
+    }
+    kernels = {}
+    for name, (total_ms, n) in sorted(timing.items()):
+        avg_ms = total_ms / n
+        entry = {"launches_per_step": n / args.steps, "avg_ms": avg_ms}
+        bound, w = work.get(name, (None, None))
+        if w:
+            if bound == "mfma":
+                a = w / (avg_ms * 1e-3) / 1e12
+                entry.update(bound="mfma", achieved=a, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s",
+                             frac=a / PEAK_MFMA_BF16_TFLOPS)
+            else:
+                a = w / (avg_ms * 1e-3) / 1e9
+                entry.update(bound="hbm", achieved=a, peak=PEAK_HBM_GBS, unit="GB/s", frac=a / PEAK_HBM_GBS)
+        kernels[name] = entry
+    dom = kernels["gemm_gate_up_swiglu"]
+    roofline = {"kernel": "gemm_gate_up_swiglu", "bound": "mfma", "achieved": dom["achieved"],
+                "peak": dom["peak"], "unit": "TFLOP/s", "frac": dom["frac"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
+
+    gemm_ms = sum(timing[n][0] for n in ("gemm_gate_up_swiglu", "gemm_down")) / args.steps
+    enum_names = ("gram", "routing_prep", "subset_score", "loss_reduce_argmin")
+    enum_ms = sum(timing[n][0] for n in enum_names if n in timing) / args.steps
+    skip_names = ("gemm_gate_up_swiglu_routed", "gemm_down_routed", "skip_route_dispatch", "skip_combine")
+    skip_ms = sum(timing[n][0] for n in skip_names if n in timing) / args.steps
+    out = {
+        "metric": "subset·tokens scored/sec (whole hot path: expert outputs + enumeration r=6,4 + skip forward)",
+        "value": value, "unit": "subset·tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: E={E} top-{k} H={H} F={F} T={T} r={list(cfg.rs)}; "
+                               f"skip forward on {T_skip} tokens, beta={beta:.4f}",
+                   "input_backend": layer["backend"], "seed": cfg.seed},
+        "expert_gemm_tflops": 6.0 * T * H * F * E / (gemm_ms * 1e-3) / 1e12,
+        "expert_gemm_ms": gemm_ms,
+        "enumerate_subset_tokens_per_s": n_sub * T / (enum_ms * 1e-3),
+        "enumerate_ms": enum_ms,
+        "skip_forward_tokens_per_s": T_skip / (skip_ms * 1e-3) if skip_ms else None,
+        "skip_forward_ms": skip_ms,
+        "skip_fraction": 1.0 - (slots - T_skip) / T_skip,
+        "argmin": {str(r): int(results[r][1].item()) for r in cfg.rs},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, layer, Y, logits, torch, wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,125 @@
+/*
+ * moeprune -- expert-subset scoring and dynamic skipping for one MoE layer on
+ * AMD MI355X (gfx950).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * Notation follows the paper: n = E experts, k experts per token, r experts kept,
+ * hidden size H, SwiGLU ffn size F, T tokens.
+ *
+ * Conventions shared by every entry point
+ *   - All arrays are row-major and contiguous.  Pointers named below are DEVICE
+ *     pointers unless a comment says "host".
+ *   - Weights are stored out-features x in-features (y = x W^T).  W1 is the
+ *     SiLU-gated branch, W3 the linear branch, W2 the down projection.
+ *   - `dt` is the storage type of x, the weights, Y and out.  Router logits are
+ *     always fp32.  bf16 operands are multiplied exactly and accumulated in fp32.
+ *   - Ownership: the caller owns every buffer, including the workspace `ws`
+ *     (size from the matching *_workspace query, 256-byte aligned).  The library
+ *     allocates no device memory and keeps no pointer after the call returns.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t, NULL = the default
+ *     stream) and the call returns without waiting for it; outputs are valid
+ *     once the caller has synchronised the stream.
+ *   - Return value: a moep_status.  Nothing throws or aborts across the ABI.
+ *     After a non-zero status moep_last_error() describes it.  Inputs holding
+ *     NaN or Inf give unspecified results.
+ *   - Same inputs give bitwise identical outputs (no floating-point atomics).
+ *   - Shape limits: 1 <= E <= 32; T >= 0 (T = 0 is a valid empty batch);
+ *     for MOEP_BF16, H and F must be multiples of 64; for MOEP_F32, multiples of 4.
+ */
+#ifndef MOEPRUNE_H
+#define MOEPRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOEP_OK = 0,
+  MOEP_EINVAL = 1,       /* null pointer, size or parameter out of range      */
+  MOEP_EUNSUPPORTED = 2, /* valid request this build has no kernel for        */
+  MOEP_EWORKSPACE = 3,   /* workspace missing, misaligned or too small        */
+  MOEP_EHIP = 4          /* a HIP runtime call or kernel launch failed        */
+} moep_status;
+
+typedef enum { MOEP_F32 = 0, MOEP_BF16 = 1 } moep_dtype;
+
+/* ---- host-only helpers (no GPU needed) ------------------------------------ */
+
+/* Number of kept-expert subsets, C(E,r) (Sec. 3.2).  -1 if E or r is out of range. */
+int64_t moep_num_subsets(int E, int r);
+
+/* Subset index <-> kept mask.  Subsets are indexed in lexicographic order of
+ * their sorted expert-index tuples (index 0 keeps experts 0..r-1); bit e of the
+ * mask is set iff expert e is kept.  `mask_out` is a host pointer.
+ * unrank returns a moep_status; rank returns the index, or -1 if the mask does
+ * not have exactly r bits below bit E. */
+int moep_subset_unrank(int E, int r, int64_t idx, uint32_t* mask_out);
+int64_t moep_subset_rank(int E, int r, uint32_t mask);
+
+/* Message for the calling thread's last non-zero status (static storage, host). */
+const char* moep_last_error(void);
+
+/* ---- moe_expert_outputs ---------------------------------------------------- */
+/* Sec. 3.1: router logits l = x Wgate^T and the SwiGLU output of EVERY expert on
+ * EVERY token, Y[e,t,:] = (silu(x_t W1[e]^T) * (x_t W3[e]^T)) W2[e]^T -- the
+ * quantities from which Eq. 2 and every pruned layer of Sec. 3.2 are formed.
+ *   x [T,H], Wgate [E,H], W1 [E,F,H], W3 [E,F,H], W2 [E,H,F]   (dt)
+ *   logits [T,E] fp32 (out), Y [E,T,H] dt (out)
+ * The intermediate silu(.)*(.) is rounded to dt once, between the two GEMMs.
+ * Workspace: one [T,F] dt matrix. */
+size_t moe_expert_outputs_workspace(int64_t T, int E, int H, int F, moep_dtype dt);
+int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3,
+                       const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
+                       float* logits, void* Y, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- prune_enumerate ------------------------------------------------------- */
+/* Sec. 3.2, Eq. 3: for each of the C(E,r) kept sets C, route every token to its
+ * top-min(k,r) experts among C (compare logits; ties to the lower index), weight
+ * them by Eq. 1, and accumulate || F'(x,C) - F(x) ||^2 over all tokens and hidden
+ * units, F(x) being Eq. 2 on the same logits and Y.
+ *   logits [T,E] fp32, Y [E,T,H] dt
+ *   loss [C(E,r)] fp32 (out): SQUARED Frobenius norm per subset, in subset-index order
+ *   argmin [1] int32 (out): lowest index with the smallest loss
+ *   argmin_mask [1] uint32 (out): its kept mask
+ *   unaffected_pairs [1] int64 (out, may be NULL): number of (subset, token)
+ *     pairs whose pruned routing equals the full routing (they contribute 0 exactly)
+ * Computed through the per-token Gram matrix G_t = Y_t Y_t^T: with d = pruned
+ * weights - full weights the error is d^T G_t d, the same real number as Eq. 3.
+ * C(E,r) must not exceed 2^24.  T = 0 gives all-zero losses and argmin 0. */
+size_t prune_enumerate_workspace(int64_t T, int E, int H, int k, int r, moep_dtype dt);
+int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt,
+                    int k, int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                    int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- moe_forward_skip ------------------------------------------------------ */
+/* Sec. 3.3 with the output of App. A.2, k = 2: per token take the top-2 experts
+ * e0, e1; skip e1 iff w_e1 < beta * w_e0, decided as (l_e1 - l_e0) < ln(beta) in
+ * fp32 (beta = 0 never skips); out = E_e0(x) for skipped tokens, else Eq. 2.
+ * Only routed (token, expert) pairs are pushed through an expert.
+ *   x, Wgate, W1, W3, W2 as above; beta >= 0
+ *   out [T,H] dt (out), skip_mask [T] uint8 (out, 1 = second expert skipped)
+ *   logits_out [T,E] fp32 (out, may be NULL): the router logits used, bit-identical
+ *     to those moe_expert_outputs returns for the same x and Wgate
+ *   top2_out [T,2] int32 (out, may be NULL): e0, e1 per token
+ * k must be 2 (MOEP_EUNSUPPORTED otherwise). */
+size_t moe_forward_skip_workspace(int64_t T, int E, int H, int F, moep_dtype dt);
+int moe_forward_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
+                     const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                     float beta, void* out, uint8_t* skip_mask, float* logits_out,
+                     int32_t* top2_out, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- per-kernel timing (for benchmarks) ------------------------------------ */
+/* While enabled, every kernel launch is bracketed by HIP events on its stream.
+ * moep_timing_collect waits for the recorded events, adds them up per kernel and
+ * clears the record; `names`/`total_ms`/`launches` are host arrays of `cap`
+ * entries (names: static strings).  Returns the number of kernels seen, or -1.
+ * At most 8192 launches are recorded between collects; later ones go untimed. */
+int moep_timing_enable(int on);
+int moep_timing_collect(const char** names, double* total_ms, int64_t* launches, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEPRUNE_H */

@@ -1,0 +1,227 @@
+"""ctypes binding of libmoeprune.so: argument marshalling only.
+
+Every function here has the name and meaning of the C entry point it calls (see
+include/moeprune.h); torch supplies device memory and the stream, nothing else.
+Importing this module raises if the library has not been built -- there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_size_t, c_uint32, c_void_p
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmoeprune.so")
+
+MOEP_F32, MOEP_BF16 = 0, 1
+_STATUS = {0: "MOEP_OK", 1: "MOEP_EINVAL", 2: "MOEP_EUNSUPPORTED", 3: "MOEP_EWORKSPACE", 4: "MOEP_EHIP"}
+
+EXPORTS = (
+    "moep_num_subsets", "moep_subset_unrank", "moep_subset_rank", "moep_last_error",
+    "moe_expert_outputs_workspace", "moe_expert_outputs",
+    "prune_enumerate_workspace", "prune_enumerate",
+    "moe_forward_skip_workspace", "moe_forward_skip",
+    "moep_timing_enable", "moep_timing_collect",
+)
+
+
+class MoepError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2402_14800_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.moep_num_subsets.restype = c_int64
+    lib.moep_num_subsets.argtypes = [c_int, c_int]
+    lib.moep_subset_unrank.restype = c_int
+    lib.moep_subset_unrank.argtypes = [c_int, c_int, c_int64, POINTER(c_uint32)]
+    lib.moep_subset_rank.restype = c_int64
+    lib.moep_subset_rank.argtypes = [c_int, c_int, c_uint32]
+    lib.moep_last_error.restype = c_char_p
+    lib.moep_last_error.argtypes = []
+    lib.moe_expert_outputs_workspace.restype = c_size_t
+    lib.moe_expert_outputs_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int]
+    lib.moe_expert_outputs.restype = c_int
+    lib.moe_expert_outputs.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int,
+                                                        c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.prune_enumerate_workspace.restype = c_size_t
+    lib.prune_enumerate_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, c_int]
+    lib.prune_enumerate.restype = c_int
+    lib.prune_enumerate.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
+                                    c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.moe_forward_skip_workspace.restype = c_size_t
+    lib.moe_forward_skip_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int]
+    lib.moe_forward_skip.restype = c_int
+    lib.moe_forward_skip.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_float,
+                                                      c_void_p, c_void_p, c_void_p, c_void_p,
+                                                      c_void_p, c_size_t, c_void_p]
+    lib.moep_timing_enable.restype = c_int
+    lib.moep_timing_enable.argtypes = [c_int]
+    lib.moep_timing_collect.restype = c_int
+    lib.moep_timing_collect.argtypes = [POINTER(c_char_p), POINTER(c_double), POINTER(c_int64), c_int]
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise MoepError(status, _lib.moep_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MOEP_F32
+    if t.dtype == torch.bfloat16:
+        return MOEP_BF16
+    raise TypeError(f"unsupported storage dtype {t.dtype}: use float32 or bfloat16")
+
+
+def _dev(*tensors: torch.Tensor) -> torch.device:
+    d = tensors[0].device
+    for t in tensors:
+        if t.device != d or t.device.type != "cuda":
+            raise ValueError("all tensors must live on the same GPU")
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous (row-major)")
+    return d
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _stream(dev: torch.device):
+    return c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+
+
+def _workspace(nbytes: int, dev: torch.device, ws: Optional[torch.Tensor]) -> torch.Tensor:
+    if ws is not None:
+        if ws.dtype != torch.uint8 or ws.device != dev or not ws.is_contiguous():
+            raise ValueError("workspace must be a contiguous uint8 tensor on the same GPU")
+        return ws
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
+
+
+# ---------------------------------------------------------------- host helpers
+def num_subsets(E: int, r: int) -> int:
+    return int(_lib.moep_num_subsets(E, r))
+
+
+def subset_unrank(E: int, r: int, idx: int) -> int:
+    m = c_uint32(0)
+    _check(_lib.moep_subset_unrank(E, r, idx, ctypes.byref(m)))
+    return int(m.value)
+
+
+def subset_rank(E: int, r: int, mask: int) -> int:
+    return int(_lib.moep_subset_rank(E, r, mask))
+
+
+# ---------------------------------------------------------------- entry points
+def moe_expert_outputs_workspace(T: int, E: int, H: int, F: int, dtype_code: int) -> int:
+    return int(_lib.moe_expert_outputs_workspace(T, E, H, F, dtype_code))
+
+
+def moe_expert_outputs(x, Wgate, W1, W3, W2, logits=None, Y=None, workspace=None):
+    """logits [T,E] fp32 and Y [E,T,H] for every expert and token (asynchronous on the current stream)."""
+    dev = _dev(x, Wgate, W1, W3, W2)
+    dt = _dtype_code(x)
+    T, H = x.shape
+    E, F, _ = W1.shape
+    assert Wgate.shape == (E, H) and W3.shape == (E, F, H) and W2.shape == (E, H, F)
+    assert all(_dtype_code(t) == dt for t in (Wgate, W1, W3, W2))
+    if logits is None:
+        logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+    if Y is None:
+        Y = torch.empty((E, T, H), dtype=x.dtype, device=dev)
+    need = _lib.moe_expert_outputs_workspace(T, E, H, F, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.moe_expert_outputs(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt,
+                                   _ptr(logits), _ptr(Y), _ptr(ws), ws.numel(), _stream(dev)))
+    return logits, Y
+
+
+def prune_enumerate_workspace(T: int, E: int, H: int, k: int, r: int, dtype_code: int) -> int:
+    return int(_lib.prune_enumerate_workspace(T, E, H, k, r, dtype_code))
+
+
+def prune_enumerate(logits, Y, k: int, r: int, workspace=None, count_unaffected: bool = True):
+    """loss [C(E,r)] fp32, argmin [1] int32, argmin_mask [1] (int32 view of the uint32 mask),
+    unaffected_pairs [1] int64 (or None).  Device tensors; asynchronous on the current stream."""
+    dev = _dev(logits, Y)
+    dt = _dtype_code(Y)
+    E, T, H = Y.shape
+    assert logits.shape == (T, E) and logits.dtype == torch.float32
+    n = num_subsets(E, r)
+    if n < 0:
+        raise MoepError(1, f"r={r} out of range [1, E={E}]")
+    loss = torch.empty((n,), dtype=torch.float32, device=dev)
+    argmin = torch.empty((1,), dtype=torch.int32, device=dev)
+    amask = torch.empty((1,), dtype=torch.int32, device=dev)
+    unaffected = torch.empty((1,), dtype=torch.int64, device=dev) if count_unaffected else None
+    need = _lib.prune_enumerate_workspace(T, E, H, k, r, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.prune_enumerate(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
+                                _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
+    return loss, argmin, amask, unaffected
+
+
+def moe_forward_skip_workspace(T: int, E: int, H: int, F: int, dtype_code: int) -> int:
+    return int(_lib.moe_forward_skip_workspace(T, E, H, F, dtype_code))
+
+
+def moe_forward_skip(x, Wgate, W1, W3, W2, beta: float, k: int = 2, workspace=None,
+                     want_logits: bool = True, want_top2: bool = True):
+    """out [T,H], skip_mask [T] uint8, logits [T,E] fp32 (or None), top2 [T,2] int32 (or None)."""
+    dev = _dev(x, Wgate, W1, W3, W2)
+    dt = _dtype_code(x)
+    T, H = x.shape
+    E, F, _ = W1.shape
+    assert Wgate.shape == (E, H) and W3.shape == (E, F, H) and W2.shape == (E, H, F)
+    out = torch.empty((T, H), dtype=x.dtype, device=dev)
+    skip = torch.empty((T,), dtype=torch.uint8, device=dev)
+    logits = torch.empty((T, E), dtype=torch.float32, device=dev) if want_logits else None
+    top2 = torch.empty((T, 2), dtype=torch.int32, device=dev) if want_top2 else None
+    need = _lib.moe_forward_skip_workspace(T, E, H, F, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.moe_forward_skip(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt, k,
+                                 c_float(beta), _ptr(out), _ptr(skip), _ptr(logits), _ptr(top2),
+                                 _ptr(ws), ws.numel(), _stream(dev)))
+    return out, skip, logits, top2
+
+
+# ---------------------------------------------------------------- kernel timing
+def kernel_timing_enable(on: bool = True) -> None:
+    _check(_lib.moep_timing_enable(1 if on else 0))
+
+
+def kernel_timing_collect() -> Dict[str, Tuple[float, int]]:
+    """{kernel name: (total milliseconds, launches)} since the last collect; waits for the GPU."""
+    cap = 64
+    names = (c_char_p * cap)()
+    ms = (c_double * cap)()
+    cnt = (c_int64 * cap)()
+    n = _lib.moep_timing_collect(names, ms, cnt, cap)
+    if n < 0:
+        raise MoepError(4, _lib.moep_last_error().decode())
+    return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+def kernel_timing_reset() -> None:
+    kernel_timing_collect()

@@ -1,0 +1,313 @@
+// Host side of libmoeprune: the C ABI declared in include/moeprune.h.
+// Argument checks, subset rank/unrank, workspace carving, per-kernel timing and the
+// sequencing of kernel launches.  No arithmetic of the method runs here.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace moep {
+
+// ---------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+// ---------------------------------------------------------------- subsets
+int64_t binomial(int n, int r) {
+  if (r < 0 || r > n) return 0;
+  if (r > n - r) r = n - r;
+  int64_t c = 1;
+  for (int i = 1; i <= r; ++i) c = c * (n - r + i) / i;   // exact: c is C(n-r+i, i) after step i
+  return c;
+}
+
+// Lexicographic unranking of sorted r-tuples over {0..E-1}: walking the experts in
+// ascending order, C(E-1-e, rem-1) subsets put e as their next smallest element.
+uint32_t unrank_mask(int E, int r, int64_t idx) {
+  uint32_t mask = 0;
+  int rem = r;
+  for (int e = 0; e < E && rem > 0; ++e) {
+    int64_t with_e = binomial(E - 1 - e, rem - 1);
+    if (idx < with_e) { mask |= 1u << e; --rem; }
+    else idx -= with_e;
+  }
+  return mask;
+}
+
+// ---------------------------------------------------------------- timing
+namespace {
+struct TimingState {
+  std::mutex mu;
+  bool on = false;
+  struct Rec { const char* name; hipEvent_t start, stop; bool used; };
+  std::vector<Rec> pool;      // events created once, on enable
+  int next = 0;
+};
+TimingState g_timing;
+constexpr int kMaxTimed = 8192;
+}  // namespace
+
+Timed::Timed(const char* kernel_name, hipStream_t s) : slot(-1), stream(s) {
+  TimingState& t = g_timing;
+  if (!t.on) return;
+  std::lock_guard<std::mutex> lk(t.mu);
+  if (!t.on || t.next >= (int)t.pool.size()) return;
+  slot = t.next++;
+  t.pool[slot].name = kernel_name;
+  t.pool[slot].used = true;
+  (void)hipEventRecord(t.pool[slot].start, stream);
+}
+
+Timed::~Timed() {
+  if (slot < 0) return;
+  (void)hipEventRecord(g_timing.pool[slot].stop, stream);
+}
+
+static bool valid_shape(int64_t T, int E, int H, int F, moep_dtype dt, const char* who) {
+  if (dt != MOEP_F32 && dt != MOEP_BF16) { fail(MOEP_EINVAL, "%s: unknown dtype %d", who, (int)dt); return false; }
+  if (T < 0 || T > (int64_t)1 << 30) { fail(MOEP_EINVAL, "%s: T=%lld out of range [0, 2^30]", who, (long long)T); return false; }
+  if (E < 1 || E > 32) { fail(MOEP_EINVAL, "%s: E=%d out of range [1, 32]", who, E); return false; }
+  if (H < 1 || (F < 1)) { fail(MOEP_EINVAL, "%s: H=%d, F=%d must be positive", who, H, F); return false; }
+  return true;
+}
+
+static int check_alignment(int H, int F, moep_dtype dt, const char* who) {
+  int q = dt == MOEP_BF16 ? 64 : 4;
+  if (H % q || F % q)
+    return fail(MOEP_EUNSUPPORTED, "%s: H=%d and F=%d must be multiples of %d for this dtype", who, H, F, q);
+  if ((int64_t)H > 65536 || (int64_t)F > 262144)
+    return fail(MOEP_EUNSUPPORTED, "%s: H=%d or F=%d beyond the supported maximum", who, H, F);
+  return MOEP_OK;
+}
+
+static int check_ws(const void* ws, size_t ws_bytes, size_t need, const char* who) {
+  if (need == 0) return MOEP_OK;
+  if (!ws) return fail(MOEP_EWORKSPACE, "%s: workspace is NULL, %zu bytes needed", who, need);
+  if ((uintptr_t)ws & 255) return fail(MOEP_EWORKSPACE, "%s: workspace must be 256-byte aligned", who);
+  if (ws_bytes < need) return fail(MOEP_EWORKSPACE, "%s: workspace has %zu bytes, %zu needed", who, ws_bytes, need);
+  return MOEP_OK;
+}
+
+static int run_gemm(const GemmArgs& g, moep_dtype dt, hipStream_t s, const char* name) {
+  return dt == MOEP_BF16 ? launch_gemm_bf16(g, s, name) : launch_gemm_f32(g, s, name);
+}
+
+}  // namespace moep
+
+using namespace moep;
+
+extern "C" {
+
+const char* moep_last_error(void) { return g_err; }
+
+int64_t moep_num_subsets(int E, int r) {
+  if (E < 1 || E > 32 || r < 1 || r > E) return -1;
+  return binomial(E, r);
+}
+
+int moep_subset_unrank(int E, int r, int64_t idx, uint32_t* mask_out) {
+  int64_t n = moep_num_subsets(E, r);
+  if (n < 0) return fail(MOEP_EINVAL, "moep_subset_unrank: need 1 <= r <= E <= 32 (E=%d, r=%d)", E, r);
+  if (!mask_out) return fail(MOEP_EINVAL, "moep_subset_unrank: mask_out is NULL");
+  if (idx < 0 || idx >= n) return fail(MOEP_EINVAL, "moep_subset_unrank: index %lld not in [0, %lld)", (long long)idx, (long long)n);
+  *mask_out = unrank_mask(E, r, idx);
+  return MOEP_OK;
+}
+
+int64_t moep_subset_rank(int E, int r, uint32_t mask) {
+  if (moep_num_subsets(E, r) < 0) return -1;
+  if (E < 32 && (mask >> E)) return -1;
+  if (__builtin_popcount(mask) != r) return -1;
+  int64_t idx = 0;
+  int rem = r;
+  for (int e = 0; e < E && rem > 0; ++e) {
+    if (mask & (1u << e)) --rem;
+    else idx += binomial(E - 1 - e, rem - 1);   // all subsets whose next element is e come first
+  }
+  return idx;
+}
+
+// ------------------------------------------------------------------ timing
+int moep_timing_enable(int on) {
+  TimingState& t = g_timing;
+  std::lock_guard<std::mutex> lk(t.mu);
+  if (on && t.pool.empty()) {
+    t.pool.resize(kMaxTimed);
+    for (auto& r : t.pool) {
+      r.used = false;
+      r.name = nullptr;
+      if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
+        t.pool.clear();
+        return fail(MOEP_EHIP, "moep_timing_enable: hipEventCreate failed");
+      }
+    }
+  }
+  t.on = on != 0;
+  return MOEP_OK;
+}
+
+int moep_timing_collect(const char** names, double* total_ms, int64_t* launches, int cap) {
+  TimingState& t = g_timing;
+  std::lock_guard<std::mutex> lk(t.mu);
+  if (!names || !total_ms || !launches || cap <= 0) {
+    fail(MOEP_EINVAL, "moep_timing_collect: NULL array or cap <= 0");
+    return -1;
+  }
+  int n = 0;
+  for (int i = 0; i < t.next; ++i) {
+    auto& r = t.pool[i];
+    if (!r.used) continue;
+    r.used = false;
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) {
+      fail(MOEP_EHIP, "moep_timing_collect: event query failed for %s", r.name);
+      t.next = 0;
+      return -1;
+    }
+    int j = 0;
+    while (j < n && strcmp(names[j], r.name) != 0) ++j;
+    if (j == n) {
+      if (n == cap) continue;
+      names[n] = r.name; total_ms[n] = 0.0; launches[n] = 0; ++n;
+    }
+    total_ms[j] += ms;
+    launches[j] += 1;
+  }
+  t.next = 0;
+  return n;
+}
+
+// ------------------------------------------------------------------ moe_expert_outputs
+size_t moe_expert_outputs_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {
+  if (!valid_shape(T, E, H, F, dt, "moe_expert_outputs_workspace")) return 0;
+  return align256((size_t)T * (size_t)F * dtype_size(dt));
+}
+
+int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3,
+                       const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
+                       float* logits, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "moe_expert_outputs";
+  if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
+  if (int st = check_alignment(H, F, dt, who)) return st;
+  if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (T == 0) return MOEP_OK;
+  if (!x || !logits || !Y) return fail(MOEP_EINVAL, "%s: NULL x, logits or Y", who);
+  if (int st = check_ws(ws, ws_bytes, moe_expert_outputs_workspace(T, E, H, F, dt), who)) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const size_t es = dtype_size(dt);
+
+  if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
+  for (int e = 0; e < E; ++e) {
+    GemmArgs up;                                  // h = silu(x W1[e]^T) * (x W3[e]^T)
+    up.A = x; up.lda = H;
+    up.B0 = (const char*)W1 + (size_t)e * F * H * es;
+    up.B1 = (const char*)W3 + (size_t)e * F * H * es;
+    up.C = ws; up.ldc = F;
+    up.M = T; up.N = F; up.K = H;
+    up.epilogue = EPI_SWIGLU;
+    if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu")) return st;
+    GemmArgs down;                                // Y[e] = h W2[e]^T
+    down.A = ws; down.lda = F;
+    down.B0 = (const char*)W2 + (size_t)e * H * F * es;
+    down.C = (char*)Y + (size_t)e * T * H * es; down.ldc = H;
+    down.M = T; down.N = H; down.K = F;
+    down.epilogue = EPI_STORE;
+    if (int st = run_gemm(down, dt, s, "gemm_down")) return st;
+  }
+  return MOEP_OK;
+}
+
+// ------------------------------------------------------------------ prune_enumerate
+size_t prune_enumerate_workspace(int64_t T, int E, int H, int k, int r, moep_dtype dt) {
+  if (!valid_shape(T, E, H, 1, dt, "prune_enumerate_workspace")) return 0;
+  EnumPlan p;
+  if (plan_enumerate(T, E, H, k, r, &p)) return 0;
+  return p.total;
+}
+
+int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt,
+                    int k, int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                    int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "prune_enumerate";
+  if (!valid_shape(T, E, H, 1, dt, who)) return MOEP_EINVAL;
+  EnumPlan p;
+  if (int st = plan_enumerate(T, E, H, k, r, &p)) return st;
+  if (H % (dt == MOEP_BF16 ? 64 : 1))
+    return fail(MOEP_EUNSUPPORTED, "%s: H=%d must be a multiple of 64 for bf16", who, H);
+  if (!loss || !argmin || !argmin_mask) return fail(MOEP_EINVAL, "%s: NULL loss, argmin or argmin_mask", who);
+  if (T > 0 && (!logits || !Y)) return fail(MOEP_EINVAL, "%s: NULL logits or Y", who);
+  if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
+  return launch_enumerate(p, logits, Y, dt, loss, argmin, argmin_mask, unaffected_pairs,
+                          (char*)ws, (hipStream_t)hip_stream);
+}
+
+// ------------------------------------------------------------------ moe_forward_skip
+size_t moe_forward_skip_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {
+  if (!valid_shape(T, E, H, F, dt, "moe_forward_skip_workspace")) return 0;
+  SkipPlan p;
+  if (plan_skip(T, E, H, F, dt, &p)) return 0;
+  return p.total;
+}
+
+int moe_forward_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
+                     const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                     float beta, void* out, uint8_t* skip_mask, float* logits_out,
+                     int32_t* top2_out, void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "moe_forward_skip";
+  if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
+  if (k != 2) return fail(MOEP_EUNSUPPORTED, "%s: only k = 2 is implemented (k=%d)", who, k);
+  if (E < 2) return fail(MOEP_EINVAL, "%s: top-2 routing needs E >= 2 (E=%d)", who, E);
+  if (!(beta >= 0.0f) || std::isinf(beta)) return fail(MOEP_EINVAL, "%s: beta must be finite and >= 0", who);
+  if (int st = check_alignment(H, F, dt, who)) return st;
+  if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (T == 0) return MOEP_OK;
+  if (!x || !out || !skip_mask) return fail(MOEP_EINVAL, "%s: NULL x, out or skip_mask", who);
+  SkipPlan p;
+  if (int st = plan_skip(T, E, H, F, dt, &p)) return st;
+  if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* w = (char*)ws;
+  const size_t es = dtype_size(dt);
+
+  float* logits = logits_out ? logits_out : (float*)(w + p.off_logits);
+  if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
+  if (int st = launch_skip_routing(p, logits, beta, skip_mask, top2_out, w, s)) return st;
+
+  GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
+  up.A = x; up.lda = H; up.a_rows = (const int32_t*)(w + p.off_slot_token);
+  up.B0 = W1; up.B1 = W3; up.b_expert_stride = (int64_t)F * H;
+  up.C = w + p.off_h; up.ldc = F;
+  up.M = p.max_slots; up.N = F; up.K = H;
+  up.epilogue = EPI_SWIGLU;
+  up.tile_expert = (const int32_t*)(w + p.off_tile_expert);
+  up.tile_row0 = (const int32_t*)(w + p.off_tile_row0);
+  up.seg_end = (const int32_t*)(w + p.off_seg_end);
+  up.max_m_tiles = p.max_tiles;
+  if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu_routed")) return st;
+
+  GemmArgs down;                    // slot_out[slot] = weight(slot) * h[slot] W2[e]^T, fp32
+  down.A = w + p.off_h; down.lda = F;
+  down.B0 = W2; down.b_expert_stride = (int64_t)H * F;
+  down.C = w + p.off_slot_out; down.ldc = H;
+  down.M = p.max_slots; down.N = H; down.K = F;
+  down.epilogue = EPI_ROWSCALE_F32;
+  down.row_scale = (const float*)(w + p.off_slot_scale);
+  down.tile_expert = up.tile_expert; down.tile_row0 = up.tile_row0; down.seg_end = up.seg_end;
+  down.max_m_tiles = p.max_tiles;
+  if (int st = run_gemm(down, dt, s, "gemm_down_routed")) return st;
+  (void)es;
+  return launch_skip_combine(p, dt, skip_mask, out, w, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+// Internal declarations shared by the host API and the kernel launchers of libmoeprune.
+// Nothing here is part of the C ABI (that is include/moeprune.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "moeprune.h"
+
+namespace moep {
+
+// ---- errors -----------------------------------------------------------------
+int fail(int status, const char* fmt, ...);   // records the thread's message, returns status
+
+#define MOEP_HIP(expr)                                                                  \
+  do {                                                                                  \
+    hipError_t _e = (expr);                                                             \
+    if (_e != hipSuccess)                                                               \
+      return ::moep::fail(MOEP_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e));    \
+  } while (0)
+
+// ---- per-kernel timing ------------------------------------------------------
+// A Timed object brackets the launches made during its lifetime with a pair of
+// HIP events on `stream` when timing is enabled; otherwise it does nothing.
+struct Timed {
+  Timed(const char* kernel_name, hipStream_t stream);
+  ~Timed();
+  int slot;
+  hipStream_t stream;
+};
+
+static inline size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t dtype_size(moep_dtype dt) { return dt == MOEP_BF16 ? 2 : 4; }
+
+// ---- GEMM: C = epilogue(A B^T), A [M,K] and B [N,K] both K-contiguous ---------
+enum GemmEpilogue {
+  EPI_STORE = 0,      // C[m,n] = acc                       (C in dt, N columns)
+  EPI_SWIGLU = 1,     // C[m,n] = silu(A B0^T) * (A B1^T)    (C in dt, N columns)
+  EPI_ROWSCALE_F32 = 2  // C[m,n] = row_scale[m] * acc        (C in fp32)
+};
+
+struct GemmArgs {
+  const void* A = nullptr;       // [rows, K], leading dimension lda (elements)
+  int64_t lda = 0;
+  const int32_t* a_rows = nullptr;  // optional: logical row m reads A row a_rows[m]
+  const void* B0 = nullptr;      // [N, K] (per expert), leading dimension K
+  const void* B1 = nullptr;      // second weight for EPI_SWIGLU
+  void* C = nullptr;             // [rows, N], leading dimension ldc (elements)
+  int64_t ldc = 0;
+  int64_t M = 0;                 // logical rows (dense mode) or upper bound on rows (grouped)
+  int N = 0, K = 0;
+  int epilogue = EPI_STORE;
+  const float* row_scale = nullptr;
+  // Grouped mode (rows partitioned into per-expert segments): tile t of the M
+  // dimension covers rows [tile_row0[t], min(tile_row0[t] + BM, seg_end[tile_expert[t]]))
+  // and multiplies with expert tile_expert[t]'s weights; tile_expert[t] < 0 = no work.
+  const int32_t* tile_expert = nullptr;
+  const int32_t* tile_row0 = nullptr;
+  const int32_t* seg_end = nullptr;     // [E] end row (exclusive) of each expert's segment
+  int64_t b_expert_stride = 0;          // elements between consecutive experts' weights
+  int64_t max_m_tiles = 0;              // grouped: number of entries in tile_expert/tile_row0
+};
+
+constexpr int GEMM_BM = 256;   // rows per tile of either GEMM implementation's grouped map
+
+int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name);
+int launch_gemm_f32(const GemmArgs& g, hipStream_t s, const char* name);
+
+// ---- router -------------------------------------------------------------------
+int launch_router(const void* x, const void* Wgate, int64_t T, int E, int H, moep_dtype dt,
+                  float* logits, hipStream_t s);
+
+// ---- enumeration ----------------------------------------------------------------
+struct EnumPlan {
+  int64_t T; int E, H, k, r;
+  int kk;            // min(k, r): experts per token in the pruned layer
+  int n_act;         // min(E, kk + E - r): rank positions that can be selected
+  int64_t n_sub;     // C(E, r)
+  int rec_floats;    // floats per token record
+  int tok_tile;      // tokens per scoring block
+  int64_t n_tok_tiles;
+  // workspace carving (byte offsets)
+  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, total;
+};
+int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p);
+int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
+                     float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
+                     char* ws, hipStream_t s);
+
+// ---- skipping ---------------------------------------------------------------------
+struct SkipPlan {
+  int64_t T; int E, H, F;
+  int64_t max_slots;     // 2 T
+  int64_t max_tiles;     // upper bound on M tiles over all experts
+  size_t off_logits, off_slot_token, off_slot_scale, off_pos, off_counts, off_seg_end,
+         off_tile_expert, off_tile_row0, off_h, off_slot_out, total;
+};
+int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, SkipPlan* p);
+int launch_skip_routing(const SkipPlan& p, const float* logits, float beta, uint8_t* skip_mask,
+                        int32_t* top2_out, char* ws, hipStream_t s);
+int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
+                        char* ws, hipStream_t s);
+
+// Host-side subset helpers (also used to fill the device mask table).
+int64_t binomial(int n, int r);
+uint32_t unrank_mask(int E, int r, int64_t idx);
+
+}  // namespace moep

@@ -1,0 +1,469 @@
+// Enumeration of kept-expert subsets (Sec. 3.2, Eq. 3) through the per-token Gram matrix.
+//
+// For token t let Y_t be the E x H matrix of its expert outputs, a the Eq. 1 weights of the full
+// layer (top-k of all experts) and b those of the layer pruned to the kept set C (top-min(k,r)
+// of C).  Then F'(x_t,C) - F(x_t) = sum_e (b_e - a_e) Y_t[e,:] and its squared norm is d^T G_t d
+// with d = b - a, G_t = Y_t Y_t^T.  The kernels:
+//
+//   gram        G_t for every token: the only pass over Y (HBM-bound).  bf16: one
+//               v_mfma_f32_16x16x32_bf16 per 16 rows x 32 hidden units, the SAME registers feeding
+//               both operands (B = A^T), two tokens per tile when E <= 8.
+//   prep        per token: stable descending order of the logits (ties -> lower index), and
+//               everything the scorer needs, moved to RANK space (position j = j-th ranked expert):
+//               exp(l_j - l_0), l_j, the full-layer weights a_j, the Gram matrix permuted to rank
+//               order (off-diagonals doubled).  Only the first n_act = min(E, min(k,r) + E - r)
+//               positions can ever be selected by a pruned layer, so only those are kept.
+//   score       lane = subset, loop over a tile of tokens.  Per token all data is wave-uniform
+//               (scalar loads); each lane walks the rank positions, takes the first min(k,r) whose
+//               expert is in its mask, forms d explicitly and evaluates d^T G d.  A pair whose
+//               selection equals the full top-k contributes exactly 0 and is counted.
+//   reduce      loss[i] = sum over token tiles of the partial sums, in a fixed order (fp64 adds).
+//   argmin      lowest index attaining the minimum; its mask by lexicographic unranking.
+#include "common.h"
+
+namespace moep {
+namespace {
+
+// ------------------------------------------------------------------ binomials / unranking
+struct BinomTable {
+  uint32_t v[33][33];
+  constexpr BinomTable() : v{} {
+    for (int n = 0; n <= 32; ++n) {
+      v[n][0] = 1;
+      for (int r = 1; r <= n; ++r) v[n][r] = v[n - 1][r - 1] + (r <= n - 1 ? v[n - 1][r] : 0);
+    }
+  }
+};
+__constant__ BinomTable c_binom = BinomTable();
+
+// Kept mask of subset `idx` in lexicographic order of sorted r-tuples over {0..E-1}.
+__device__ uint32_t unrank_device(int E, int r, uint32_t idx) {
+  uint32_t mask = 0;
+  int rem = r;
+  for (int e = 0; e < E; ++e) {
+    if (rem == 0) break;
+    const uint32_t with_e = c_binom.v[E - 1 - e][rem - 1];
+    if (idx < with_e) { mask |= 1u << e; --rem; }
+    else idx -= with_e;
+  }
+  return mask;
+}
+
+// ------------------------------------------------------------------ Gram, bf16 (MFMA)
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// EPAD = rows reserved per token inside a 16-row tile (4, 8 or 16): 16 / EPAD tokens per tile.
+template <int EPAD>
+__global__ __launch_bounds__(256) void gram_bf16_16_kernel(const uint4* __restrict__ Y,
+                                                           float* __restrict__ G, int64_t T, int E,
+                                                           int H) {
+  constexpr int TPT = 16 / EPAD;
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t t0 = tile * TPT;
+  if (t0 >= T) return;
+  const int row = lane & 15, kg = lane >> 4;           // operand row, 8-element k group
+  const int e = row % EPAD;
+  const int64_t t = t0 + row / EPAD;
+  const bool valid = e < E && t < T;
+  const int chunks = H / 8;                             // 16-byte chunks per row
+  const uint4* src = Y + ((int64_t)(valid ? e : 0) * T + (valid ? t : t0)) * chunks + kg;
+
+  f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+  const int steps = H / 32;                             // even: H is a multiple of 64
+  for (int s0 = 0; s0 < steps; s0 += 8) {
+    uint4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int s = s0 + i;
+      v[i] = (valid && s < steps) ? src[s * 4] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+      const bf16x8 a0 = __builtin_bit_cast(bf16x8, v[i]);
+      const bf16x8 a1 = __builtin_bit_cast(bf16x8, v[i + 1]);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, a0, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, a1, acc1, 0, 0, 0);
+    }
+  }
+  // Accumulator layout of the 16x16 tile: register v of lane l = row 4 (l / 16) + v, column l % 16.
+  const int col = lane & 15;
+  const int ce = col % EPAD;
+  const int64_t ct = t0 + col / EPAD;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int r = 4 * (lane >> 4) + v;
+    const int re = r % EPAD;
+    if (r / EPAD == col / EPAD && ct < T && re < E && ce < E)
+      G[(ct * E + re) * E + ce] = acc0[v] + acc1[v];
+  }
+}
+
+// E in 17..32: one token per 32x32 tile.
+__global__ __launch_bounds__(256) void gram_bf16_32_kernel(const uint4* __restrict__ Y,
+                                                           float* __restrict__ G, int64_t T, int E,
+                                                           int H) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const int row = lane & 31, kg = lane >> 5;
+  const bool valid = row < E;
+  const int chunks = H / 8;
+  const uint4* src = Y + ((int64_t)(valid ? row : 0) * T + t) * chunks + kg;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  const int steps = H / 16;
+  for (int s0 = 0; s0 < steps; s0 += 4) {
+    uint4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = valid ? src[(s0 + i) * 2] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, v[i]);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, acc, 0, 0, 0);
+    }
+  }
+  const int col = lane & 31;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    if (r < E && col < E) G[(t * E + r) * E + col] = acc[v];
+  }
+}
+
+// ------------------------------------------------------------------ Gram, fp32 storage
+__global__ __launch_bounds__(256) void gram_f32_kernel(const float* __restrict__ Y,
+                                                       float* __restrict__ G, int64_t T, int E,
+                                                       int H) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  for (int e = 0; e < E; ++e)
+    for (int f = e; f < E; ++f) {
+      const float* ye = Y + ((int64_t)e * T + t) * H;
+      const float* yf = Y + ((int64_t)f * T + t) * H;
+      float s = 0.f;
+      for (int h = lane; h < H; h += 64) s = fmaf(ye[h], yf[h], s);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+      if (lane == 0) {
+        G[(t * E + e) * E + f] = s;
+        G[(t * E + f) * E + e] = s;
+      }
+    }
+}
+
+// ------------------------------------------------------------------ record layout
+// Per token, CAP = capacity >= n_act, all fp32 unless noted:
+//   [0, CAP)            ex_j  = exp(l_j - l_0), l in rank order (0 beyond n_act)
+//   [CAP, 2 CAP)        l_j
+//   [2 CAP, 3 CAP)      a_j   = full-layer Eq. 1 weight of rank j (0 for j >= k)
+//   [3 CAP, 3 CAP + CAP (CAP + 1) / 2)   Gram in rank order, row-major upper triangle,
+//                       diagonal as is, off-diagonal entries doubled
+//   then ceil(CAP / 4) words: expert index of rank j in byte j
+__host__ __device__ constexpr int rec_tri(int cap) { return cap * (cap + 1) / 2; }
+__host__ __device__ constexpr int rec_order_off(int cap) { return 3 * cap + rec_tri(cap); }
+__host__ __device__ constexpr int rec_size(int cap) {
+  return (rec_order_off(cap) + (cap + 3) / 4 + 3) & ~3;
+}
+
+template <int EMAX>
+__global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ logits,
+                                                   const float* __restrict__ G,
+                                                   float* __restrict__ rec, int64_t T, int E,
+                                                   int k, int n_act, int cap, int rec_floats) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  float l[EMAX];
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) l[e] = e < E ? logits[t * E + e] : 0.f;
+  // rank of expert e = number of experts that precede it: larger logit, or equal and lower index
+  int rank[EMAX];
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) {
+    int c = 0;
+#pragma unroll
+    for (int f = 0; f < EMAX; ++f)
+      if (f < E && f != e) c += (l[f] > l[e] || (l[f] == l[e] && f < e)) ? 1 : 0;
+    rank[e] = e < E ? c : 255;
+  }
+  float* R = rec + t * rec_floats;
+  for (int i = 0; i < rec_floats; ++i) R[i] = 0.f;
+  uint32_t* Rord = (uint32_t*)(R + rec_order_off(cap));
+  int ord[EMAX];
+  float l0 = 0.f;
+  for (int j = 0; j < n_act; ++j) {
+    int oe = 0;
+    float lv = 0.f;
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e)
+      if (rank[e] == j) { oe = e; lv = l[e]; }
+    ord[j] = oe;
+    if (j == 0) l0 = lv;
+    R[j] = expf(lv - l0);
+    R[cap + j] = lv;
+  }
+  float den = 0.f;
+  for (int j = 0; j < k; ++j) den += R[j];
+  for (int j = 0; j < k; ++j) R[2 * cap + j] = R[j] / den;
+  int idx = 3 * cap;
+  for (int i = 0; i < cap; ++i)
+    for (int j = i; j < cap; ++j, ++idx)
+      if (i < n_act && j < n_act) {
+        const float g = G[(t * E + ord[i]) * E + ord[j]];
+        R[idx] = i == j ? g : 2.0f * g;
+      }
+  for (int w = 0; w < (cap + 3) / 4; ++w) {
+    uint32_t packed = 0;
+    for (int b = 0; b < 4; ++b) {
+      const int j = 4 * w + b;
+      if (j < n_act) packed |= (uint32_t)ord[j] << (8 * b);
+    }
+    Rord[w] = packed;
+  }
+}
+
+// ------------------------------------------------------------------ scoring
+template <int CAP>
+__global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ rec, int64_t T,
+                                                    int tok_tile, int E, int r, int kk, int kfull,
+                                                    int n_act, uint32_t n_sub,
+                                                    float* __restrict__ partial,
+                                                    uint32_t* __restrict__ partial_cnt) {
+  constexpr int RS = rec_size(CAP);
+  constexpr int OFF_L = CAP, OFF_A = 2 * CAP, OFF_G = 3 * CAP, OFF_O = rec_order_off(CAP);
+  const uint32_t sub = blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = sub < n_sub;
+  // Idle lanes keep every expert: their selection always equals the full one and costs nothing.
+  const uint32_t mask = live ? unrank_device(E, r, sub) : 0xffffffffu;
+  const uint32_t full_bits = kk != kfull ? 0u : (kfull >= 32 ? 0xffffffffu : (1u << kfull) - 1u);   // r < k: never "same"
+  const int64_t t_begin = (int64_t)blockIdx.y * tok_tile;
+  const int64_t t_end = t_begin + tok_tile < T ? t_begin + tok_tile : T;
+
+  float total = 0.f;
+  uint32_t same_cnt = 0;
+  for (int64_t t = t_begin; t < t_end; ++t) {
+    const float* R = rec + t * RS;                       // wave-uniform
+    const uint32_t* Rord = (const uint32_t*)(R + OFF_O);
+    float w[CAP];
+    float sum = 0.f;
+    uint32_t bits = 0;
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < CAP; ++j) {
+      w[j] = 0.f;
+      if (j < n_act) {
+        const uint32_t e = (Rord[j >> 2] >> (8 * (j & 3))) & 0xffu;
+        const bool take = ((mask >> e) & 1u) && cnt < kk;
+        cnt += take ? 1 : 0;
+        bits |= take ? (1u << j) : 0u;
+        w[j] = take ? R[j] : 0.f;
+        sum += w[j];
+      }
+    }
+    if (sum < 1e-30f) {
+      // Every selected logit lies far below the token's maximum: redo Eq. 1 relative to the
+      // largest SELECTED logit (the first one taken), as the definition has it.
+      float m = 0.f;
+      bool have = false;
+#pragma unroll
+      for (int j = 0; j < CAP; ++j)
+        if (j < n_act && ((bits >> j) & 1u) && !have) { m = R[OFF_L + j]; have = true; }
+      sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < CAP; ++j) {
+        w[j] = (j < n_act && ((bits >> j) & 1u)) ? __expf(R[OFF_L + j] - m) : 0.f;
+        sum += w[j];
+      }
+    }
+    const float inv = __builtin_amdgcn_rcpf(sum);
+    float d[CAP];
+#pragma unroll
+    for (int j = 0; j < CAP; ++j) d[j] = fmaf(w[j], inv, -R[OFF_A + j]);
+    float q = 0.f;
+    int gi = OFF_G;
+#pragma unroll
+    for (int i = 0; i < CAP; ++i) {
+      float u = 0.f;
+#pragma unroll
+      for (int j = i; j < CAP; ++j, ++gi) u = fmaf(R[gi], d[j], u);
+      q = fmaf(d[i], u, q);
+    }
+    const bool same = bits == full_bits;
+    same_cnt += (same && live) ? 1u : 0u;
+    total += same ? 0.f : q;
+  }
+  if (live) {
+    partial[(int64_t)blockIdx.y * n_sub + sub] = total;
+    partial_cnt[(int64_t)blockIdx.y * n_sub + sub] = same_cnt;
+  }
+}
+
+// ------------------------------------------------------------------ reduce + argmin
+__global__ __launch_bounds__(256) void zero_i64_kernel(unsigned long long* p) { *p = 0ull; }
+
+__global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ partial,
+                                                     const uint32_t* __restrict__ partial_cnt,
+                                                     int64_t n_tiles, uint32_t n_sub,
+                                                     float* __restrict__ loss,
+                                                     unsigned long long* unaffected) {
+  const uint32_t sub = blockIdx.x * 256 + threadIdx.x;
+  if (sub >= n_sub) return;
+  double s = 0.0;
+  unsigned long long c = 0;
+  for (int64_t i = 0; i < n_tiles; ++i) {
+    s += (double)partial[i * n_sub + sub];
+    c += partial_cnt[i * n_sub + sub];
+  }
+  loss[sub] = (float)s;
+  if (unaffected && c) atomicAdd(unaffected, c);      // integer: the sum does not depend on order
+}
+
+__global__ __launch_bounds__(1024) void argmin_kernel(const float* __restrict__ loss,
+                                                      uint32_t n_sub, int E, int r,
+                                                      int32_t* argmin, uint32_t* argmin_mask) {
+  __shared__ float sv[1024];
+  __shared__ uint32_t si[1024];
+  float best = INFINITY;
+  uint32_t bi = 0xffffffffu;
+  for (uint32_t i = threadIdx.x; i < n_sub; i += 1024) {
+    const float v = loss[i];
+    if (v < best || bi == 0xffffffffu) { best = v; bi = i; }   // ascending i: first minimum wins
+  }
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int off = 512; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      const float v = sv[threadIdx.x + off];
+      const uint32_t i = si[threadIdx.x + off];
+      const float mv = sv[threadIdx.x];
+      const uint32_t mi = si[threadIdx.x];
+      if (i != 0xffffffffu && (mi == 0xffffffffu || v < mv || (v == mv && i < mi))) {
+        sv[threadIdx.x] = v;
+        si[threadIdx.x] = i;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const uint32_t i = si[0] == 0xffffffffu ? 0u : si[0];
+    *argmin = (int32_t)i;
+    *argmin_mask = unrank_device(E, r, i);
+  }
+}
+
+int capacity_for(int n_act) {
+  const int caps[] = {2, 4, 6, 8, 12, 16, 32};
+  for (int c : caps)
+    if (n_act <= c) return c;
+  return -1;
+}
+
+}  // namespace
+
+int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
+  if (k < 1 || k > E) return fail(MOEP_EINVAL, "prune_enumerate: k=%d out of range [1, E=%d]", k, E);
+  if (r < 1 || r > E) return fail(MOEP_EINVAL, "prune_enumerate: r=%d out of range [1, E=%d]", r, E);
+  p->T = T; p->E = E; p->H = H; p->k = k; p->r = r;
+  p->kk = k < r ? k : r;
+  const int n_act = p->kk + E - r;
+  p->n_act = n_act < E ? n_act : E;
+  p->n_sub = binomial(E, r);
+  if (p->n_sub > ((int64_t)1 << 24))
+    return fail(MOEP_EUNSUPPORTED, "prune_enumerate: C(%d,%d) = %lld subsets exceeds 2^24", E, r, (long long)p->n_sub);
+  const int cap = capacity_for(p->n_act);
+  p->rec_floats = rec_size(cap);
+  // Aim for a few thousand scoring workgroups; tiles of 32..256 tokens.
+  const int64_t sub_blocks = ceil_div(p->n_sub, p->n_sub <= 64 ? 64 : 256);
+  int tile = 256;
+  while (tile > 32 && sub_blocks * ceil_div(T, tile) < 4096) tile >>= 1;
+  p->tok_tile = tile;
+  p->n_tok_tiles = ceil_div(T, tile);
+  if (p->n_tok_tiles > 65535) { p->tok_tile = (int)ceil_div(T, 65535); p->n_tok_tiles = ceil_div(T, p->tok_tile); }
+  size_t off = 0;
+  p->off_gram = off; off += align256((size_t)T * E * E * sizeof(float));
+  p->off_rec = off; off += align256((size_t)T * p->rec_floats * sizeof(float));
+  p->off_masks = off;
+  p->off_partial = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(float));
+  p->off_partial_cnt = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(uint32_t));
+  p->total = off > 0 ? off : 256;
+  return MOEP_OK;
+}
+
+template <int CAP>
+static void launch_score(const EnumPlan& p, const float* rec, float* partial, uint32_t* pcnt,
+                         hipStream_t s) {
+  const int threads = p.n_sub <= 64 ? 64 : 256;
+  dim3 grid((unsigned)ceil_div(p.n_sub, threads), (unsigned)p.n_tok_tiles);
+  hipLaunchKernelGGL(score_kernel<CAP>, grid, dim3(threads), 0, s, rec, p.T, p.tok_tile, p.E, p.r,
+                     p.kk, p.k, p.n_act, (uint32_t)p.n_sub, partial, pcnt);
+}
+
+int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
+                     float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
+                     char* ws, hipStream_t s) {
+  float* G = (float*)(ws + p.off_gram);
+  float* rec = (float*)(ws + p.off_rec);
+  float* partial = (float*)(ws + p.off_partial);
+  uint32_t* pcnt = (uint32_t*)(ws + p.off_partial_cnt);
+  const int cap = capacity_for(p.n_act);
+  if (p.T > 0) {
+    {
+      Timed t("gram", s);
+      const unsigned per_tok_blocks = (unsigned)ceil_div(p.T, 4);
+      if (dt == MOEP_BF16) {
+        if (p.E <= 4)
+          hipLaunchKernelGGL(gram_bf16_16_kernel<4>, dim3((unsigned)ceil_div(p.T, 16)), dim3(256), 0, s, (const uint4*)Y, G, p.T, p.E, p.H);
+        else if (p.E <= 8)
+          hipLaunchKernelGGL(gram_bf16_16_kernel<8>, dim3((unsigned)ceil_div(p.T, 8)), dim3(256), 0, s, (const uint4*)Y, G, p.T, p.E, p.H);
+        else if (p.E <= 16)
+          hipLaunchKernelGGL(gram_bf16_16_kernel<16>, dim3(per_tok_blocks), dim3(256), 0, s, (const uint4*)Y, G, p.T, p.E, p.H);
+        else
+          hipLaunchKernelGGL(gram_bf16_32_kernel, dim3(per_tok_blocks), dim3(256), 0, s, (const uint4*)Y, G, p.T, p.E, p.H);
+      } else {
+        hipLaunchKernelGGL(gram_f32_kernel, dim3(per_tok_blocks), dim3(256), 0, s, (const float*)Y, G, p.T, p.E, p.H);
+      }
+      MOEP_HIP(hipGetLastError());
+    }
+    {
+      Timed t("routing_prep", s);
+      const dim3 grid((unsigned)ceil_div(p.T, 256));
+      if (p.E <= 8)
+        hipLaunchKernelGGL(prep_kernel<8>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
+      else if (p.E <= 16)
+        hipLaunchKernelGGL(prep_kernel<16>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
+      else
+        hipLaunchKernelGGL(prep_kernel<32>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
+      MOEP_HIP(hipGetLastError());
+    }
+    {
+      Timed t("subset_score", s);
+      switch (cap) {
+        case 2: launch_score<2>(p, rec, partial, pcnt, s); break;
+        case 4: launch_score<4>(p, rec, partial, pcnt, s); break;
+        case 6: launch_score<6>(p, rec, partial, pcnt, s); break;
+        case 8: launch_score<8>(p, rec, partial, pcnt, s); break;
+        case 12: launch_score<12>(p, rec, partial, pcnt, s); break;
+        case 16: launch_score<16>(p, rec, partial, pcnt, s); break;
+        case 32: launch_score<32>(p, rec, partial, pcnt, s); break;
+        default: return fail(MOEP_EUNSUPPORTED, "prune_enumerate: no scorer for %d active ranks", p.n_act);
+      }
+      MOEP_HIP(hipGetLastError());
+    }
+  }
+  {
+    Timed t("loss_reduce_argmin", s);
+    if (unaffected) hipLaunchKernelGGL(zero_i64_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)unaffected);
+    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)ceil_div(p.n_sub, 256)), dim3(256), 0, s, partial, pcnt,
+                       p.T > 0 ? p.n_tok_tiles : 0, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
+    hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, s, loss, (uint32_t)p.n_sub, p.E, p.r, argmin, argmin_mask);
+    MOEP_HIP(hipGetLastError());
+  }
+  return MOEP_OK;
+}
+
+}  // namespace moep

@@ -1,0 +1,266 @@
+// bf16 GEMM for gfx950: C = epilogue(A B^T), A [M,K] and B [N,K] K-contiguous, fp32 accumulate
+// on the MFMA units (v_mfma_f32_32x32x16_bf16).
+//
+// Tiling.  One workgroup of 512 threads (8 wavefronts, 2 along M x 4 along N) owns a
+// 256 x 256 tile of the accumulator and walks K in steps of 64.  Each wavefront owns a
+// 128 x 64 sub-tile = 4 x 2 MFMA tiles of 32 x 32 (128 accumulator registers per lane).
+// Operand tiles are staged through LDS (two buffers, one barrier per K step); rows are padded
+// from 128 to 144 bytes so that the 16-byte fragment reads of consecutive rows fall into
+// different banks.  Global loads for step i+1 are issued before the MFMAs of step i.
+//
+// SwiGLU mode (the gate/up projection of one expert, Sec. 3.1): the 256 B-rows of a tile are
+// 128 rows of W1 followed by the SAME 128 rows of W3, and each wavefront's two N sub-tiles are
+// (gate, up) for the same 32 output columns, so silu(gate) * up is formed in registers and only
+// the product is written, rounded once to bf16.
+//
+// Grouped mode (dynamic skipping, Sec. 3.3): M tiles are looked up in a device-side tile map
+// (expert, first row); rows of A may be gathered through an index list.
+//
+// Workgroup order: consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with a
+// private L2.  Ids are remapped so that every XCD works on a contiguous run of tiles, ordered
+// 8 M-tiles deep before moving along N, so that the tiles in flight on one XCD share operand panels.
+#include "common.h"
+
+namespace moep {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int THREADS = 512;
+constexpr int ROW_BYTES = 144;                 // 64 bf16 + 16 bytes of padding
+constexpr int TILE_BYTES = BM * ROW_BYTES;     // one operand tile (BM == BN)
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // A tile then B tile
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;     // 147456
+static_assert(BM == GEMM_BM, "grouped tile maps are built for 256-row tiles");
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+struct KArgs {
+  const uint4* A; const uint4* B0; const uint4* B1;
+  const int32_t* a_rows;
+  void* C;
+  const float* row_scale;
+  const int32_t* tile_expert; const int32_t* tile_row0; const int32_t* seg_end;
+  int64_t M, ldc;
+  uint32_t lda_chunks, ldb_chunks;   // leading dimensions in 16-byte chunks
+  int64_t b_expert_chunks;           // expert stride of B in 16-byte chunks
+  int N, K;
+  int m_tiles, n_tiles;
+};
+
+template <int EPI>
+__global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  // ---- which tile -------------------------------------------------------------
+  const uint32_t nblk = gridDim.x;
+  uint32_t bid = blockIdx.x;
+  {  // XCD-aware remap: ids i, i+8, i+16, ... run on XCD i % 8; give each XCD a contiguous run.
+    const uint32_t per = nblk >> 3, rem = nblk & 7;
+    const uint32_t xcd = bid & 7, j = bid >> 3;
+    bid = xcd * per + (xcd < rem ? xcd : rem) + j;
+  }
+  constexpr uint32_t GROUP_M = 8;
+  const uint32_t group_sz = GROUP_M * p.n_tiles;
+  const uint32_t group = bid / group_sz;
+  const uint32_t first_m = group * GROUP_M;
+  const uint32_t gm = min((uint32_t)p.m_tiles - first_m, GROUP_M);
+  const uint32_t in_group = bid - group * group_sz;
+  const int tm = first_m + in_group % gm;
+  const int tn = in_group / gm;
+
+  int64_t row0, row_end;
+  const uint4* B0 = p.B0;
+  const uint4* B1 = p.B1;
+  if (p.tile_expert) {
+    const int e = p.tile_expert[tm];
+    if (e < 0) return;                               // uniform over the workgroup
+    row0 = p.tile_row0[tm];
+    row_end = p.seg_end[e];
+    B0 += (int64_t)e * p.b_expert_chunks;
+    if (EPI == EPI_SWIGLU) B1 += (int64_t)e * p.b_expert_chunks;
+  } else {
+    row0 = (int64_t)tm * BM;
+    row_end = p.M;
+  }
+
+  // ---- global -> LDS staging: thread owns chunk column c of rows r0 + 64 i ---------
+  const int c = tid & 7;
+  const int r0 = tid >> 3;
+  uint32_t a_off[4], b_off[4];
+  const uint4* b_ptr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int64_t r = row0 + r0 + 64 * i;
+    if (r >= row_end) r = row_end - 1;               // tail rows re-read the last valid row
+    const int64_t src = p.a_rows ? (int64_t)p.a_rows[r] : r;
+    a_off[i] = (uint32_t)src * p.lda_chunks + c;
+    int n;
+    const uint4* base;
+    if (EPI == EPI_SWIGLU) {
+      const int rr = r0 + 64 * i;                    // rows 0..127 gate, 128..255 up
+      n = tn * 128 + (rr & 127);
+      base = rr < 128 ? B0 : B1;
+    } else {
+      n = tn * BN + r0 + 64 * i;
+      base = B0;
+    }
+    if (n >= p.N) n = p.N - 1;
+    b_ptr[i] = base;
+    b_off[i] = (uint32_t)n * p.ldb_chunks + c;
+  }
+  const int st_off = r0 * ROW_BYTES + c * 16;        // + 64 i rows, + TILE_BYTES for B
+
+  uint4 ra[4], rb[4];
+  auto load_global = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      ra[i] = p.A[a_off[i] + (uint32_t)kt * 8u];
+      rb[i] = b_ptr[i][b_off[i] + (uint32_t)kt * 8u];
+    }
+  };
+  auto store_lds = [&](int buf) {
+    char* base = lds + buf * STAGE_BYTES + st_off;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *(uint4*)(base + i * 64 * ROW_BYTES) = ra[i];
+      *(uint4*)(base + TILE_BYTES + i * 64 * ROW_BYTES) = rb[i];
+    }
+  };
+
+  // ---- fragment addresses ---------------------------------------------------------
+  // MFMA 32x32x16: lane l supplies row (l & 31) and the 8 k-values 8 (l >> 5) .. + 7 of A,
+  // and the same for B (as [N,K]).  Per K step of 64 there are 4 such slices (kk).
+  const int frow = lane & 31, fk = lane >> 5;
+  const int a_frag = (wm * 128 + frow) * ROW_BYTES + fk * 16;
+  int b_frag[2];
+  if (EPI == EPI_SWIGLU) {
+    b_frag[0] = TILE_BYTES + (wn * 32 + frow) * ROW_BYTES + fk * 16;
+    b_frag[1] = TILE_BYTES + (128 + wn * 32 + frow) * ROW_BYTES + fk * 16;
+  } else {
+    b_frag[0] = TILE_BYTES + (wn * 64 + frow) * ROW_BYTES + fk * 16;
+    b_frag[1] = TILE_BYTES + (wn * 64 + 32 + frow) * ROW_BYTES + fk * 16;
+  }
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk = p.K / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const bool more = kt + 1 < nk;
+    if (more) load_global(kt + 1);
+    const char* st = lds + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 a[4], b[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        a[i] = *(const bf16x8*)(st + a_frag + i * 32 * ROW_BYTES + kk * 32);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = *(const bf16x8*)(st + b_frag[j] + kk * 32);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) store_lds((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue ---------------------------------------------------------------------
+  // Accumulator layout of a 32x32 tile: register v of lane l holds
+  // row 8 (v / 4) + 4 (l / 32) + (v % 4), column l % 32.
+  const int col_in = lane & 31;
+  const int row_in = 4 * (lane >> 5);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t r = row0 + wm * 128 + i * 32 + 8 * (v >> 2) + row_in + (v & 3);
+      if (r >= row_end) continue;
+      if (EPI == EPI_SWIGLU) {
+        const int n = tn * 128 + wn * 32 + col_in;
+        if (n < p.N) {
+          const float g = acc[i][0][v], u = acc[i][1][v];
+          const float h = g / (1.0f + __expf(-g)) * u;
+          ((uint16_t*)p.C)[r * p.ldc + n] = f32_to_bf16_rne(h);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int n = tn * BN + wn * 64 + j * 32 + col_in;
+          if (n >= p.N) continue;
+          if (EPI == EPI_STORE) ((uint16_t*)p.C)[r * p.ldc + n] = f32_to_bf16_rne(acc[i][j][v]);
+          else ((float*)p.C)[r * p.ldc + n] = p.row_scale[r] * acc[i][j][v];
+        }
+      }
+    }
+  }
+}
+
+template <int EPI>
+int launch(const KArgs& k, uint32_t blocks, hipStream_t s) {
+  static bool attr_set = false;   // raising the dynamic LDS limit is per function, once
+  if (!attr_set) {
+    MOEP_HIP(hipFuncSetAttribute((const void*)gemm_bf16_kernel<EPI>,
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, dim3(blocks), dim3(THREADS), LDS_BYTES, s, k);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+}  // namespace
+
+int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name) {
+  if (g.K % BK || g.K <= 0) return fail(MOEP_EUNSUPPORTED, "%s: K=%d must be a positive multiple of %d", name, g.K, BK);
+  if (g.lda % 8 || g.ldc <= 0) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
+  if (g.M <= 0 || g.N <= 0) return MOEP_OK;
+  KArgs k;
+  k.A = (const uint4*)g.A; k.B0 = (const uint4*)g.B0; k.B1 = (const uint4*)g.B1;
+  k.a_rows = g.a_rows; k.C = g.C; k.row_scale = g.row_scale;
+  k.tile_expert = g.tile_expert; k.tile_row0 = g.tile_row0; k.seg_end = g.seg_end;
+  k.M = g.M; k.ldc = g.ldc;
+  k.lda_chunks = (uint32_t)(g.lda / 8); k.ldb_chunks = (uint32_t)(g.K / 8);
+  k.b_expert_chunks = g.b_expert_stride / 8;
+  k.N = g.N; k.K = g.K;
+  const int64_t m_tiles = g.tile_expert ? g.max_m_tiles : ceil_div(g.M, BM);
+  const int64_t n_tiles = g.epilogue == EPI_SWIGLU ? ceil_div(g.N, 128) : ceil_div(g.N, BN);
+  // Row offsets are kept as 32-bit counts of 16-byte chunks.
+  const int64_t a_rows_max = g.a_rows ? g.M : m_tiles * BM;   // gathered rows index x, checked by the caller
+  if (a_rows_max * (g.lda / 8) >= ((int64_t)1 << 32) || (int64_t)g.N * (g.K / 8) >= ((int64_t)1 << 32))
+    return fail(MOEP_EUNSUPPORTED, "%s: operand larger than 64 GiB", name);
+  if (m_tiles * n_tiles >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "%s: too many tiles", name);
+  k.m_tiles = (int)m_tiles; k.n_tiles = (int)n_tiles;
+  const uint32_t blocks = (uint32_t)(m_tiles * n_tiles);
+  Timed t(name, s);
+  switch (g.epilogue) {
+    case EPI_STORE: return launch<EPI_STORE>(k, blocks, s);
+    case EPI_SWIGLU: return launch<EPI_SWIGLU>(k, blocks, s);
+    case EPI_ROWSCALE_F32: return launch<EPI_ROWSCALE_F32>(k, blocks, s);
+  }
+  return fail(MOEP_EINVAL, "%s: unknown epilogue %d", name, g.epilogue);
+}
+
+}  // namespace moep

@@ -1,0 +1,114 @@
+// Router logits l[t,e] = sum_h x[t,h] Wgate[e,h] (Sec. 3.1), fp32 result.
+//
+// Bandwidth-bound: x is read once, Wgate (E x H) stays in L1/L2.  A wavefront takes four
+// tokens at a time; lane l owns the h-chunks l, l + 64, ... of every row (16 bytes each), keeps
+// 4 x E partial sums and a butterfly of shuffles adds them across the lanes.  The summation
+// order for a token depends on nothing but H, so the same token gives the same bits in any batch
+// -- moe_expert_outputs and moe_forward_skip rely on that.
+#include "common.h"
+
+namespace moep {
+namespace {
+
+constexpr int TOK = 4;
+
+template <bool BF16>
+struct Chunk;                      // one 16-byte load and its fp32 expansion
+template <>
+struct Chunk<true> {
+  static constexpr int N = 8;
+  __device__ static void load(const void* row, int chunk, float (&v)[8]) {
+    const uint4 u = ((const uint4*)row)[chunk];
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+      v[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xffff0000u);
+    }
+  }
+};
+template <>
+struct Chunk<false> {
+  static constexpr int N = 4;
+  __device__ static void load(const void* row, int chunk, float (&v)[4]) {
+    const float4 f = ((const float4*)row)[chunk];
+    v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+  }
+};
+
+template <bool BF16, int EMAX>
+__global__ __launch_bounds__(256) void router_kernel(const void* __restrict__ x,
+                                                     const void* __restrict__ Wgate,
+                                                     float* __restrict__ logits, int64_t T, int E,
+                                                     int H) {
+  using C = Chunk<BF16>;
+  constexpr int ES = BF16 ? 2 : 4;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t n_waves = (int64_t)gridDim.x * 4;
+  const int chunks = H / C::N;
+  const size_t row_bytes = (size_t)H * ES;
+
+  for (int64_t t0 = wave * TOK; t0 < T; t0 += n_waves * TOK) {
+    float acc[TOK][EMAX];
+#pragma unroll
+    for (int i = 0; i < TOK; ++i)
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) acc[i][e] = 0.f;
+
+    for (int c = lane; c < chunks; c += 64) {
+      float xv[TOK][C::N];
+#pragma unroll
+      for (int i = 0; i < TOK; ++i) {
+        const int64_t t = t0 + i < T ? t0 + i : T - 1;
+        C::load((const char*)x + t * row_bytes, c, xv[i]);
+      }
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) {
+        if (e < E) {
+          float wv[C::N];
+          C::load((const char*)Wgate + e * row_bytes, c, wv);
+#pragma unroll
+          for (int i = 0; i < TOK; ++i)
+#pragma unroll
+            for (int j = 0; j < C::N; ++j) acc[i][e] = fmaf(xv[i][j], wv[j], acc[i][e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < TOK; ++i)
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) {
+        if (e < E) {
+          float v = acc[i][e];
+#pragma unroll
+          for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+          if (lane == 0 && t0 + i < T) logits[(t0 + i) * E + e] = v;
+        }
+      }
+  }
+}
+
+template <bool BF16>
+int launch_t(const void* x, const void* Wgate, int64_t T, int E, int H, float* logits, hipStream_t s) {
+  const int64_t groups = ceil_div(T, TOK);
+  const unsigned blocks = (unsigned)(ceil_div(groups, 4) < 16384 ? ceil_div(groups, 4) : 16384);
+  if (E <= 8) hipLaunchKernelGGL((router_kernel<BF16, 8>), dim3(blocks), dim3(256), 0, s, x, Wgate, logits, T, E, H);
+  else if (E <= 16) hipLaunchKernelGGL((router_kernel<BF16, 16>), dim3(blocks), dim3(256), 0, s, x, Wgate, logits, T, E, H);
+  else hipLaunchKernelGGL((router_kernel<BF16, 32>), dim3(blocks), dim3(256), 0, s, x, Wgate, logits, T, E, H);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+}  // namespace
+
+int launch_router(const void* x, const void* Wgate, int64_t T, int E, int H, moep_dtype dt,
+                  float* logits, hipStream_t s) {
+  if (T <= 0) return MOEP_OK;
+  if (H % (dt == MOEP_BF16 ? 8 : 4)) return fail(MOEP_EUNSUPPORTED, "router: H=%d not a multiple of the 16-byte chunk", H);
+  Timed t("router_logits", s);
+  return dt == MOEP_BF16 ? launch_t<true>(x, Wgate, T, E, H, logits, s)
+                         : launch_t<false>(x, Wgate, T, E, H, logits, s);
+}
+
+}  // namespace moep

@@ -1,0 +1,232 @@
+// Dynamic skipping, top-2 (Sec. 3.3; output per App. A.2): routing, dispatch and combine.
+// The expert FFNs themselves are the grouped GEMMs (see gemm_bf16.hip / gemm_f32.hip).
+//
+//   route    per token: top-2 experts by logit (ties -> lower index), delta = l_e1 - l_e0 in fp32,
+//            skip iff delta < theta = fp32(ln beta) (theta = -inf for beta = 0), weights
+//            a0 = 1 / (1 + rho), a1 = rho / (1 + rho), rho = exp(delta); a0 = 1 when skipped.
+//            Also counts, per block of 256 tokens, the rows each expert receives.
+//   scan     turns the counts into each (block, expert)'s first slot, each expert's segment end,
+//            and the map from 256-row M tiles to (expert, first row) that the grouped GEMMs walk.
+//   scatter  writes slot -> token and slot -> weight lists and token -> slot positions.  Within an
+//            expert's segment the rows are in ascending token order, so the result is reproducible.
+//   combine  out[t] = slot_out[pos0] (+ slot_out[pos1] unless skipped); the down projection has
+//            already multiplied each slot by its weight.  No atomics anywhere on this path.
+#include <cmath>
+
+#include "common.h"
+
+namespace moep {
+namespace {
+
+constexpr int RB = 256;     // tokens per routing block
+
+__global__ __launch_bounds__(RB) void route_kernel(const float* __restrict__ logits, int64_t T,
+                                                   int E, float theta, uint8_t* __restrict__ skip_mask,
+                                                   int32_t* __restrict__ top2,
+                                                   float* __restrict__ tw, int32_t* __restrict__ counts) {
+  __shared__ int cnt[32];
+  if (threadIdx.x < 32) cnt[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t t = (int64_t)blockIdx.x * RB + threadIdx.x;
+  if (t < T) {
+    const float* l = logits + t * E;
+    int e0 = 0, e1 = -1;
+    float l0 = l[0], l1 = -INFINITY;
+    for (int e = 1; e < E; ++e) {          // strict comparisons: the lower index wins a tie
+      const float v = l[e];
+      if (v > l0) { l1 = l0; e1 = e0; l0 = v; e0 = e; }
+      else if (e1 < 0 || v > l1) { l1 = v; e1 = e; }
+    }
+    const float delta = l1 - l0;
+    const bool skip = delta < theta;
+    const float rho = expf(delta);
+    const float a0 = skip ? 1.0f : 1.0f / (1.0f + rho);
+    const float a1 = skip ? 0.0f : rho / (1.0f + rho);
+    skip_mask[t] = skip ? 1 : 0;
+    top2[2 * t] = e0;
+    top2[2 * t + 1] = e1;
+    tw[2 * t] = a0;
+    tw[2 * t + 1] = a1;
+    atomicAdd(&cnt[e0], 1);
+    if (!skip) atomicAdd(&cnt[e1], 1);
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < E) counts[(int64_t)blockIdx.x * E + threadIdx.x] = cnt[threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ counts, int64_t n_blocks,
+                                                   int E, int32_t* __restrict__ seg_end,
+                                                   int32_t* __restrict__ tile_expert,
+                                                   int32_t* __restrict__ tile_row0, int max_tiles) {
+  __shared__ int total[32], begin[33];
+  __shared__ int n_tiles;
+  const int e = threadIdx.x;
+  if (e < E) {
+    int s = 0;
+    for (int64_t b = 0; b < n_blocks; ++b) s += counts[b * E + e];
+    total[e] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int i = 0; i < E; ++i) { begin[i] = run; run += total[i]; }
+    begin[E] = run;
+    int idx = 0;
+    for (int i = 0; i < E; ++i)
+      for (int row = begin[i]; row < begin[i + 1] && idx < max_tiles; row += GEMM_BM) {
+        tile_expert[idx] = i;
+        tile_row0[idx] = row;
+        ++idx;
+      }
+    n_tiles = idx;
+  }
+  __syncthreads();
+  if (e < E) {
+    int run = begin[e];
+    for (int64_t b = 0; b < n_blocks; ++b) {
+      const int c = counts[b * E + e];
+      counts[b * E + e] = run;
+      run += c;
+    }
+    seg_end[e] = run;
+  }
+  for (int i = n_tiles + threadIdx.x; i < max_tiles; i += blockDim.x) {
+    tile_expert[i] = -1;
+    tile_row0[i] = 0;
+  }
+}
+
+__global__ __launch_bounds__(RB) void scatter_kernel(const int32_t* __restrict__ top2,
+                                                     const float* __restrict__ tw,
+                                                     const uint8_t* __restrict__ skip_mask,
+                                                     const int32_t* __restrict__ base, int64_t T,
+                                                     int E, int32_t* __restrict__ slot_token,
+                                                     float* __restrict__ slot_scale,
+                                                     int32_t* __restrict__ pos) {
+  __shared__ int wave_cnt[RB / 64][32];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * RB + threadIdx.x;
+  const bool live = t < T;
+  const int e0 = live ? top2[2 * t] : -1;
+  const int e1 = (live && !skip_mask[t]) ? top2[2 * t + 1] : -1;
+  const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int rank0 = 0, rank1 = 0;
+  for (int e = 0; e < E; ++e) {
+    const unsigned long long b0 = __ballot(e0 == e), b1 = __ballot(e1 == e);
+    const int before = __popcll(b0 & below) + __popcll(b1 & below);
+    if (e0 == e) rank0 = before;
+    if (e1 == e) rank1 = before;
+    if (lane == 0) wave_cnt[wave][e] = __popcll(b0) + __popcll(b1);
+  }
+  __syncthreads();
+  if (!live) return;
+  int p0 = base[(int64_t)blockIdx.x * E + e0] + rank0;
+  for (int w = 0; w < wave; ++w) p0 += wave_cnt[w][e0];
+  slot_token[p0] = (int32_t)t;
+  slot_scale[p0] = tw[2 * t];
+  pos[2 * t] = p0;
+  int p1 = -1;
+  if (e1 >= 0) {
+    p1 = base[(int64_t)blockIdx.x * E + e1] + rank1;
+    for (int w = 0; w < wave; ++w) p1 += wave_cnt[w][e1];
+    slot_token[p1] = (int32_t)t;
+    slot_scale[p1] = tw[2 * t + 1];
+  }
+  pos[2 * t + 1] = p1;
+}
+
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__ slot_out,
+                                                      const int32_t* __restrict__ pos, int64_t T,
+                                                      int H4, void* __restrict__ out) {
+  const int64_t n = T * H4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t t = i / H4;
+    const int c = (int)(i - t * H4);
+    const int p0 = pos[2 * t], p1 = pos[2 * t + 1];
+    float4 v = slot_out[(int64_t)p0 * H4 + c];
+    if (p1 >= 0) {
+      const float4 u = slot_out[(int64_t)p1 * H4 + c];
+      v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    if (BF16) {
+      uint2 o;
+      o.x = bf16_rne(v.x) | (bf16_rne(v.y) << 16);
+      o.y = bf16_rne(v.z) | (bf16_rne(v.w) << 16);
+      ((uint2*)out)[i] = o;
+    } else {
+      ((float4*)out)[i] = v;
+    }
+  }
+}
+
+}  // namespace
+
+int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, SkipPlan* p) {
+  if (2 * T >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "moe_forward_skip: T too large");
+  p->T = T; p->E = E; p->H = H; p->F = F;
+  p->max_slots = 2 * T;
+  p->max_tiles = ceil_div(2 * T, GEMM_BM) + E;
+  const int64_t n_blocks = ceil_div(T, RB);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  p->off_logits = take((size_t)T * E * 4);
+  p->off_slot_token = take((size_t)p->max_slots * 4);
+  p->off_slot_scale = take((size_t)p->max_slots * 4);
+  p->off_pos = take((size_t)T * 2 * 4 * 3);            // pos, top2, weights: [T,2] each
+  p->off_counts = take((size_t)n_blocks * E * 4);
+  p->off_seg_end = take((size_t)E * 4);
+  p->off_tile_expert = take((size_t)p->max_tiles * 4);
+  p->off_tile_row0 = take((size_t)p->max_tiles * 4);
+  p->off_h = take((size_t)p->max_slots * F * dtype_size(dt));
+  p->off_slot_out = take((size_t)p->max_slots * H * 4);
+  p->total = off > 0 ? off : 256;
+  return MOEP_OK;
+}
+
+int launch_skip_routing(const SkipPlan& p, const float* logits, float beta, uint8_t* skip_mask,
+                        int32_t* top2_out, char* ws, hipStream_t s) {
+  const int64_t T = p.T;
+  int32_t* pos = (int32_t*)(ws + p.off_pos);
+  int32_t* top2 = top2_out ? top2_out : pos + 2 * T;
+  float* tw = (float*)(pos + 4 * T);
+  int32_t* counts = (int32_t*)(ws + p.off_counts);
+  const int64_t n_blocks = ceil_div(T, RB);
+  const float theta = beta > 0.0f ? (float)std::log((double)beta) : -INFINITY;
+  Timed t("skip_route_dispatch", s);
+  hipLaunchKernelGGL(route_kernel, dim3((unsigned)n_blocks), dim3(RB), 0, s, logits, T, p.E, theta,
+                     skip_mask, top2, tw, counts);
+  hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, counts, n_blocks, p.E,
+                     (int32_t*)(ws + p.off_seg_end), (int32_t*)(ws + p.off_tile_expert),
+                     (int32_t*)(ws + p.off_tile_row0), (int)p.max_tiles);
+  hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)n_blocks), dim3(RB), 0, s, top2, tw, skip_mask,
+                     counts, T, p.E, (int32_t*)(ws + p.off_slot_token),
+                     (float*)(ws + p.off_slot_scale), pos);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
+                        char* ws, hipStream_t s) {
+  (void)skip_mask;
+  const int H4 = p.H / 4;
+  const int64_t n = p.T * H4;
+  const unsigned blocks = (unsigned)(ceil_div(n, 256) < 65536 ? ceil_div(n, 256) : 65536);
+  Timed t("skip_combine", s);
+  if (dt == MOEP_BF16)
+    hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(256), 0, s,
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out);
+  else
+    hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(256), 0, s,
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+}  // namespace moep

@@ -1,0 +1,236 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle.
+
+Tolerances (from the benchmark spec): subset indices, masks, argmin, top-2 ids and
+skip masks bit-exact; losses within 1e-3 relative; logits within 1e-3 * max|logits|
+absolute; expert outputs / layer outputs within 2e-2 relative (per-row L2, and max-abs
+against the largest reference magnitude).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2402_14800_amd as pkg
+from paper_2402_14800_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LOSS_RTOL = 1e-3
+OUT_RTOL = 2e-2
+
+
+def check_outputs(got: np.ndarray, ref: np.ndarray, what: str):
+    """Rows along the last axis: relative L2 error per row and max-abs error vs max|ref|."""
+    err = np.linalg.norm(got - ref, axis=-1)
+    nrm = np.linalg.norm(ref, axis=-1)
+    floor = 1e-6 * max(float(nrm.max()), 1e-30)       # rows that are (nearly) zero in the reference
+    rel = err / np.maximum(nrm, floor)
+    assert rel.max() <= OUT_RTOL, f"{what}: worst row relative L2 error {rel.max():.3e}"
+    assert np.abs(got - ref).max() <= OUT_RTOL * np.abs(ref).max(), f"{what}: max-abs error"
+
+
+def check_losses(got: np.ndarray, ref: np.ndarray):
+    assert got.shape == ref.shape
+    bad = np.abs(got - ref) > LOSS_RTOL * np.abs(ref)
+    assert not bad.any(), f"loss mismatch at {np.nonzero(bad)[0][:5]}: {got[bad][:5]} vs {ref[bad][:5]}"
+
+
+def check_argmin(amin_gpu: int, loss_ref: np.ndarray, loss_gpu: np.ndarray):
+    """The GPU argmin must be the oracle's, or a subset whose oracle loss ties the minimum within
+    the loss tolerance; and it must be the lowest index attaining the GPU's own minimum."""
+    amin_ref = int(np.argmin(loss_ref))
+    assert amin_gpu == int(np.argmin(loss_gpu))
+    if amin_gpu != amin_ref:
+        assert abs(loss_ref[amin_gpu] - loss_ref[amin_ref]) <= LOSS_RTOL * abs(loss_ref[amin_ref])
+
+
+def run_enumerate(logits_t, Y_t, k, r):
+    loss, amin, amask, unaff = pkg.prune_enumerate(logits_t, Y_t, k, r)
+    torch.cuda.synchronize()
+    return (loss.cpu().numpy().astype(np.float64), int(amin.item()),
+            int(amask.item()) & 0xFFFFFFFF, int(unaff.item()))
+
+
+def tie_free(logits: np.ndarray) -> bool:
+    s = np.sort(logits, axis=1)
+    return bool(np.all(s[:, 1:] != s[:, :-1]))
+
+
+# ------------------------------------------------------------------ prune_enumerate
+ENUM_CASES = [
+    # E, k, r, T, H, dtype
+    (4, 2, 2, 512, 64, "f32"),
+    (4, 2, 2, 512, 64, "bf16"),
+    (4, 2, 4, 100, 64, "bf16"),       # r = E
+    (4, 3, 2, 77, 128, "bf16"),       # r < k
+    (5, 1, 3, 301, 64, "bf16"),       # k = 1, odd E
+    (8, 2, 6, 1000, 256, "bf16"),     # ragged token count (token pairs, scoring tiles)
+    (8, 2, 4, 1001, 192, "bf16"),     # odd T: last Gram tile holds one token
+    (8, 2, 7, 333, 64, "f32"),
+    (8, 2, 1, 129, 64, "bf16"),
+    (8, 8, 8, 64, 64, "bf16"),        # k = r = E
+    (16, 4, 12, 300, 128, "bf16"),
+    (16, 4, 8, 130, 64, "bf16"),      # 12870 subsets
+    (12, 3, 6, 90, 64, "bf16"),
+    (20, 2, 18, 70, 64, "bf16"),      # E > 16: 32-row Gram tiles
+    (6, 2, 4, 1, 64, "bf16"),         # a single token
+]
+
+
+@pytest.mark.parametrize("E,k,r,T,H,dtype", ENUM_CASES)
+def test_prune_enumerate_matches_oracle(E, k, r, T, H, dtype):
+    bias = 0.5 if E == 16 else 0.0
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, dtype, seed=1000 + 31 * E + r, bias_var=bias, device=DEV)
+    loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, k, r)
+    logits, Y = wl.to_f64(logits_t), wl.to_f64(Y_t)
+    ref, ref_amin, ref_masks = oracle.prune_enumerate(logits, Y, k, r)
+    assert len(loss) == math.comb(E, r)
+    check_losses(loss, ref)
+    check_argmin(amin, ref, loss)
+    assert amask == int(ref_masks[amin]) == pkg.subset_unrank(E, r, amin)
+    if r == E:
+        assert loss.tolist() == [0.0] and amin == 0
+    assert tie_free(logits)
+    assert unaff == (T * math.comb(E - k, r - k) if r >= k else 0)
+
+
+def test_prune_enumerate_is_deterministic_and_handles_empty_batch():
+    logits_t, Y_t = wl.make_enumeration_inputs(8, 4096, 256, "bf16", seed=5, device=DEV)
+    a = pkg.prune_enumerate(logits_t, Y_t, 2, 4)
+    b = pkg.prune_enumerate(logits_t, Y_t, 2, 4)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[3], b[3])
+    loss, amin, amask, unaff = pkg.prune_enumerate(logits_t[:0].contiguous(), Y_t[:, :0].contiguous(), 2, 6)
+    torch.cuda.synchronize()
+    assert loss.tolist() == [0.0] * 28 and amin.item() == 0 and amask.item() == 0b111111 and unaff.item() == 0
+
+
+def test_prune_enumerate_ties_and_planted_argmin():
+    E, T, H = 6, 200, 64
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, "bf16", seed=9, device=DEV)
+    logits_t[:, [1, 4]] = -1e9                 # never routed to: dropping exactly these costs nothing
+    logits_t[::7, 2] = logits_t[::7, 0]        # exact ties between experts 0 and 2
+    loss, amin, amask, _ = run_enumerate(logits_t, Y_t, 2, 4)
+    ref, ref_amin, masks = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), 2, 4)
+    check_losses(loss, ref)
+    assert amin == ref_amin == oracle.kept_subsets(E, 4).index((0, 2, 3, 5)) and loss[amin] == 0.0
+    assert amask == 0b101101
+    # Subsets whose survivors all sit at -1e9 still need finite Eq. 1 weights.
+    loss2, _, _, _ = run_enumerate(logits_t, Y_t, 2, 2)
+    ref2, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), 2, 2)
+    assert np.all(np.isfinite(loss2))
+    check_losses(loss2, ref2)
+
+
+def test_prune_enumerate_relabelling_and_scale():
+    E, T, H = 8, 512, 128
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, "bf16", seed=11, device=DEV)
+    loss, _, _, _ = run_enumerate(logits_t, Y_t, 2, 5)
+    perm = torch.tensor(np.random.default_rng(3).permutation(E), device=DEV)
+    loss_p, _, _, _ = run_enumerate(logits_t[:, perm].contiguous(), Y_t[perm].contiguous(), 2, 5)
+    np.testing.assert_allclose(np.sort(loss_p), np.sort(loss), rtol=1e-4)
+    loss_s, _, _, _ = run_enumerate(logits_t, (Y_t * 4).contiguous(), 2, 5)     # exact scaling in bf16
+    np.testing.assert_allclose(loss_s, 16.0 * loss, rtol=1e-6)
+
+
+# ------------------------------------------------------------------ moe_expert_outputs
+def small_layer(dtype, E, k, H, F, T, index=7):
+    cfg = wl.LayerConfig(f"t-{dtype}-{E}-{H}-{F}-{T}", index, dtype, E=E, k=k, H=H, F=F, T=T, rs=())
+    return cfg, wl.make_layer(cfg, device="cpu")
+
+
+def to_dev(layer):
+    return {n: (v.to(DEV) if isinstance(v, torch.Tensor) else v) for n, v in layer.items()}
+
+
+EXPERT_CASES = [
+    ("f32", 4, 64, 128, 512),        # config 1
+    ("f32", 3, 36, 52, 70),          # ragged everything (multiples of 4)
+    ("bf16", 4, 64, 128, 512),
+    ("bf16", 2, 128, 192, 300),      # ragged M tile, N tail in both GEMMs
+    ("bf16", 3, 256, 320, 257),      # one row into a second M tile
+    ("bf16", 2, 512, 1024, 1000),
+]
+
+
+@pytest.mark.parametrize("dtype,E,H,F,T", EXPERT_CASES)
+def test_moe_expert_outputs_matches_oracle(dtype, E, H, F, T):
+    cfg, layer = small_layer(dtype, E, 2, H, F, T)
+    d = to_dev(layer)
+    logits_t, Y_t = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    ref_logits, ref_Y = oracle.expert_outputs(*(wl.to_f64(layer[n]) for n in ("x", "Wgate", "W1", "W3", "W2")))
+    got_logits = logits_t.cpu().numpy().astype(np.float64)
+    assert np.abs(got_logits - ref_logits).max() <= 1e-3 * np.abs(ref_logits).max()
+    check_outputs(wl.to_f64(Y_t), ref_Y, "Y")
+    # and again: bitwise reproducible
+    logits2, Y2 = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    assert torch.equal(logits2, logits_t) and torch.equal(Y2.view(torch.int16 if dtype == "bf16" else torch.int32),
+                                                         Y_t.view(torch.int16 if dtype == "bf16" else torch.int32))
+
+
+def test_config1_end_to_end():
+    cfg = wl.CONFIGS["C1"]
+    layer = wl.make_layer(cfg, device="cpu")
+    d = to_dev(layer)
+    logits_t, Y_t = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, cfg.k, 2)
+    ref, ref_amin, masks = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), cfg.k, 2)
+    check_losses(loss, ref)
+    check_argmin(amin, ref, loss)
+    assert unaff == 512 * math.comb(2, 0)
+    # the whole pipeline against the oracle's own expert outputs (fp32 storage: tight)
+    l64, Y64 = oracle.expert_outputs(*(wl.to_f64(layer[n]) for n in ("x", "Wgate", "W1", "W3", "W2")))
+    ref_full, _, _ = oracle.prune_enumerate(l64, Y64, cfg.k, 2)
+    np.testing.assert_allclose(loss, ref_full, rtol=1e-3)
+
+
+# ------------------------------------------------------------------ moe_forward_skip
+SKIP_CASES = [
+    ("f32", 4, 64, 128, 512, None),
+    ("bf16", 4, 64, 128, 300, None),
+    ("bf16", 8, 256, 512, 1000, None),
+    ("bf16", 8, 128, 256, 700, 0.0),     # never skip: Eq. 2
+    ("bf16", 8, 128, 256, 700, 1.5),     # always skip: top-1
+    ("bf16", 5, 128, 192, 3, None),      # fewer tokens than experts: empty expert segments
+]
+
+
+@pytest.mark.parametrize("dtype,E,H,F,T,beta", SKIP_CASES)
+def test_moe_forward_skip_matches_oracle(dtype, E, H, F, T, beta):
+    cfg, layer = small_layer(dtype, E, 2, H, F, T, index=9)
+    d = to_dev(layer)
+    logits_full, _ = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    if beta is None:
+        beta = oracle.median_skip_ratio(logits_full.cpu().numpy())
+    beta = float(np.float32(beta))
+    out_t, skip_t, logits_t, top2_t = pkg.moe_forward_skip(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"], beta)
+    torch.cuda.synchronize()
+    assert torch.equal(logits_t, logits_full)                     # same router, same bits
+    args = [wl.to_f64(layer[n]) for n in ("x", "Wgate", "W1", "W3", "W2")]
+    ref_out, ref_skip, e0, e1 = oracle.forward_skip(*args, beta, logits=logits_t.cpu().numpy())
+    assert np.array_equal(skip_t.cpu().numpy().astype(bool), ref_skip)
+    top2 = top2_t.cpu().numpy()
+    assert np.array_equal(top2[:, 0], e0) and np.array_equal(top2[:, 1], e1)
+    check_outputs(wl.to_f64(out_t), ref_out, "out")
+    if beta == 0.0:
+        assert not ref_skip.any()
+    elif beta > 1.0:
+        assert ref_skip.all()
+    elif T >= 100:
+        assert abs(ref_skip.mean() - 0.5) <= 1.0 / T + 1e-9
+
+
+def test_skip_empty_batch_and_bad_k():
+    cfg, layer = small_layer("bf16", 4, 2, 64, 128, 16, index=9)
+    d = to_dev(layer)
+    out, skip, logits, top2 = pkg.moe_forward_skip(d["x"][:0].contiguous(), d["Wgate"], d["W1"], d["W3"], d["W2"], 0.5)
+    torch.cuda.synchronize()
+    assert out.shape == (0, 64) and skip.numel() == 0
+    with pytest.raises(pkg.MoepError) as ei:
+        pkg.moe_forward_skip(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"], 0.5, k=3)
+    assert ei.value.status == 2

@@ -1,0 +1,117 @@
+"""Host-side logic of the C-ABI library: loads, exports, subset indexing, argument checks.
+No kernel is launched here."""
+import ctypes
+import itertools
+import math
+import os
+import re
+
+import pytest
+
+import paper_2402_14800_amd as pkg
+from paper_2402_14800_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "moeprune.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moep?_\w+|prune_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(binding.library_path())
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+@pytest.mark.parametrize("E,r", [(4, 2), (8, 6), (8, 4), (16, 8), (16, 12), (5, 5), (7, 1), (32, 3), (3, 2)])
+def test_subset_rank_unrank_match_combinations(E, r):
+    n = pkg.num_subsets(E, r)
+    assert n == math.comb(E, r)
+    step = max(1, n // 3000)
+    combos = itertools.combinations(range(E), r)
+    for i, c in enumerate(combos):
+        if i % step and i != n - 1:
+            continue
+        mask = sum(1 << e for e in c)
+        assert pkg.subset_unrank(E, r, i) == mask
+        assert pkg.subset_rank(E, r, mask) == i
+
+
+def test_subset_helpers_reject_bad_arguments():
+    assert pkg.num_subsets(0, 1) == -1
+    assert pkg.num_subsets(33, 2) == -1
+    assert pkg.num_subsets(8, 9) == -1
+    assert pkg.num_subsets(8, 0) == -1
+    assert pkg.subset_rank(8, 2, 0b111) == -1          # wrong popcount
+    assert pkg.subset_rank(8, 2, 0b1_0000_0001) == -1  # bit beyond E
+    assert pkg.subset_rank(32, 2, 0x80000001) == 30    # (0,1)..(0,31) come first
+    with pytest.raises(pkg.MoepError) as ei:
+        pkg.subset_unrank(8, 2, 28)
+    assert ei.value.status == 1
+    with pytest.raises(pkg.MoepError):
+        pkg.subset_unrank(8, 2, -1)
+
+
+def test_workspace_queries_are_pure_host_arithmetic():
+    assert binding.moe_expert_outputs_workspace(512, 4, 64, 128, binding.MOEP_F32) == 512 * 128 * 4
+    assert binding.moe_expert_outputs_workspace(16384, 8, 1024, 3584, binding.MOEP_BF16) == 16384 * 3584 * 2
+    w6 = binding.prune_enumerate_workspace(16384, 8, 1024, 2, 6, binding.MOEP_BF16)
+    w4 = binding.prune_enumerate_workspace(16384, 8, 1024, 2, 4, binding.MOEP_BF16)
+    assert w6 >= 16384 * 64 * 4 and w4 > w6
+    assert binding.prune_enumerate_workspace(16384, 8, 1024, 2, 9, binding.MOEP_BF16) == 0   # r > E
+    assert binding.moe_forward_skip_workspace(1024, 8, 256, 512, binding.MOEP_BF16) >= 2048 * (512 * 2 + 256 * 4)
+    assert binding.prune_enumerate_workspace(0, 8, 1024, 2, 6, binding.MOEP_BF16) >= 256
+
+
+def _call_enumerate(T, E, H, dt, k, r, ptr=1 << 20, ws=1 << 20, ws_bytes=1 << 30):
+    p = ctypes.c_void_p
+    return binding._lib.prune_enumerate(p(ptr), p(ptr), T, E, H, dt, k, r, p(ptr), p(ptr), p(ptr), None,
+                                        p(ws), ws_bytes, None)
+
+
+def test_argument_errors_come_back_as_status_codes():
+    # Every call below must be rejected before anything touches a GPU or a pointer.
+    assert _call_enumerate(128, 0, 64, 1, 2, 2) == 1
+    assert _call_enumerate(128, 33, 64, 1, 2, 2) == 1
+    assert _call_enumerate(128, 8, 64, 1, 0, 2) == 1
+    assert _call_enumerate(128, 8, 64, 1, 9, 2) == 1
+    assert _call_enumerate(128, 8, 64, 1, 2, 9) == 1
+    assert _call_enumerate(-1, 8, 64, 1, 2, 2) == 1
+    assert _call_enumerate(128, 8, 64, 7, 2, 2) == 1                 # unknown dtype
+    assert _call_enumerate(128, 8, 72, 1, 2, 2) == 2                 # bf16 H not a multiple of 64
+    assert _call_enumerate(128, 30, 64, 1, 2, 15) == 2               # C(30,15) > 2^24
+    assert _call_enumerate(128, 8, 64, 1, 2, 6, ptr=0) == 1          # NULL outputs
+    assert _call_enumerate(128, 8, 64, 1, 2, 6, ws=0) == 3           # no workspace
+    assert _call_enumerate(128, 8, 64, 1, 2, 6, ws=(1 << 20) + 8) == 3   # misaligned
+    assert _call_enumerate(128, 8, 64, 1, 2, 6, ws_bytes=1024) == 3  # too small
+    assert b"workspace" in binding._lib.moep_last_error()
+
+    p = ctypes.c_void_p
+    one = p(1 << 20)
+    f = binding._lib.moe_forward_skip
+    args = lambda **kw: [one] * 5 + [kw.get("T", 64), kw.get("E", 8), kw.get("H", 64), kw.get("F", 128),
+                                     kw.get("dt", 1), kw.get("k", 2), ctypes.c_float(kw.get("beta", 0.5)),
+                                     one, one, None, None, one, 1 << 40, None]
+    assert f(*args(k=3)) == 2
+    assert f(*args(beta=-0.1)) == 1
+    assert f(*args(beta=float("nan"))) == 1
+    assert f(*args(E=1)) == 1
+    assert f(*args(H=100)) == 2
+    g = binding._lib.moe_expert_outputs
+    gargs = lambda **kw: [one] * 5 + [kw.get("T", 64), kw.get("E", 8), kw.get("H", 64), kw.get("F", 128),
+                                      kw.get("dt", 1), one, one, one, kw.get("ws", 1 << 40), None]
+    assert g(*gargs(F=100)) == 2
+    assert g(*gargs(E=40)) == 1
+    assert g(*gargs(ws=16)) == 3
+    assert g(*gargs(T=0)) == 0                                       # empty batch: nothing to do
+
+
+def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(ImportError):
+        binding._load()
