@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--workload", default="C3", choices=["C2", "C3"],
                     help="C3 = Mixtral-shaped layer (the headline); C2 = mid layer (quick check)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy before the timed region, so that a "
+                         "rocprofv3 --pmc run of this command holds a kernel of known traffic to scale "
+                         "FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
@@ -119,6 +123,13 @@ def main():
     beta = float(torch.exp(top[:, 1] - top[:, 0]).median().item()) if T_skip % 2 else \
         float(torch.exp(top[:, 1] - top[:, 0]).sort().values[T_skip // 2 - 1:T_skip // 2 + 1].mean().item())
     del lg, top
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     results = {}
 

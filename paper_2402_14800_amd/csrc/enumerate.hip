@@ -305,21 +305,36 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
 // ------------------------------------------------------------------ reduce + argmin
 __global__ __launch_bounds__(256) void zero_i64_kernel(unsigned long long* p) { *p = 0ull; }
 
+// One workgroup per subset: thread i adds the partial sums of tiles i, i + 256, ... in fp64, then a
+// tree over the 256 threads; the order depends on nothing but the tile count.
 __global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ partial,
                                                      const uint32_t* __restrict__ partial_cnt,
                                                      int64_t n_tiles, uint32_t n_sub,
                                                      float* __restrict__ loss,
                                                      unsigned long long* unaffected) {
-  const uint32_t sub = blockIdx.x * 256 + threadIdx.x;
-  if (sub >= n_sub) return;
+  __shared__ double ss[256];
+  __shared__ unsigned long long sc[256];
+  const uint32_t sub = blockIdx.x;
   double s = 0.0;
   unsigned long long c = 0;
-  for (int64_t i = 0; i < n_tiles; ++i) {
+  for (int64_t i = threadIdx.x; i < n_tiles; i += 256) {
     s += (double)partial[i * n_sub + sub];
     c += partial_cnt[i * n_sub + sub];
   }
-  loss[sub] = (float)s;
-  if (unaffected && c) atomicAdd(unaffected, c);      // integer: the sum does not depend on order
+  ss[threadIdx.x] = s;
+  sc[threadIdx.x] = c;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      ss[threadIdx.x] += ss[threadIdx.x + off];
+      sc[threadIdx.x] += sc[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    loss[sub] = (float)ss[0];
+    if (unaffected && sc[0]) atomicAdd(unaffected, sc[0]);   // integer: order does not matter
+  }
 }
 
 __global__ __launch_bounds__(1024) void argmin_kernel(const float* __restrict__ loss,
@@ -458,7 +473,7 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
   {
     Timed t("loss_reduce_argmin", s);
     if (unaffected) hipLaunchKernelGGL(zero_i64_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)unaffected);
-    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)ceil_div(p.n_sub, 256)), dim3(256), 0, s, partial, pcnt,
+    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)p.n_sub), dim3(256), 0, s, partial, pcnt,
                        p.T > 0 ? p.n_tok_tiles : 0, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
     hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, s, loss, (uint32_t)p.n_sub, p.E, p.r, argmin, argmin_mask);
     MOEP_HIP(hipGetLastError());

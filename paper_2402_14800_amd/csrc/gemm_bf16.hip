@@ -26,6 +26,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int THREADS = 512;
@@ -42,7 +43,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 }
 
 struct KArgs {
-  const uint4* A; const uint4* B0; const uint4* B1;
+  const u32x4* A; const u32x4* B0; const u32x4* B1;
   const int32_t* a_rows;
   void* C;
   const float* row_scale;
@@ -55,7 +56,8 @@ struct KArgs {
 };
 
 template <int EPI>
-__global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_bf16_kernel(KArgs p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -80,8 +82,8 @@ __global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
   const int tn = in_group / gm;
 
   int64_t row0, row_end;
-  const uint4* B0 = p.B0;
-  const uint4* B1 = p.B1;
+  const u32x4* B0 = p.B0;
+  const u32x4* B1 = p.B1;
   if (p.tile_expert) {
     const int e = p.tile_expert[tm];
     if (e < 0) return;                               // uniform over the workgroup
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
   const int c = tid & 7;
   const int r0 = tid >> 3;
   uint32_t a_off[4], b_off[4];
-  const uint4* b_ptr[4];
+  const u32x4* b_ptr[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int64_t r = row0 + r0 + 64 * i;
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
     const int64_t src = p.a_rows ? (int64_t)p.a_rows[r] : r;
     a_off[i] = (uint32_t)src * p.lda_chunks + c;
     int n;
-    const uint4* base;
+    const u32x4* base;
     if (EPI == EPI_SWIGLU) {
       const int rr = r0 + 64 * i;                    // rows 0..127 gate, 128..255 up
       n = tn * 128 + (rr & 127);
@@ -121,22 +123,20 @@ __global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
   }
   const int st_off = r0 * ROW_BYTES + c * 16;        // + 64 i rows, + TILE_BYTES for B
 
-  uint4 ra[4], rb[4];
-  auto load_global = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra[i] = p.A[a_off[i] + (uint32_t)kt * 8u];
-      rb[i] = b_ptr[i][b_off[i] + (uint32_t)kt * 8u];
-    }
-  };
-  auto store_lds = [&](int buf) {
-    char* base = lds + buf * STAGE_BYTES + st_off;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *(uint4*)(base + i * 64 * ROW_BYTES) = ra[i];
-      *(uint4*)(base + TILE_BYTES + i * 64 * ROW_BYTES) = rb[i];
-    }
-  };
+  u32x4 ra[4], rb[4];
+#define MOEP_LOAD_GLOBAL(kt)                                   \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {              \
+    ra[i] = p.A[a_off[i] + (uint32_t)(kt) * 8u];               \
+    rb[i] = b_ptr[i][b_off[i] + (uint32_t)(kt) * 8u];          \
+  }
+#define MOEP_STORE_LDS(buf)                                                  \
+  {                                                                          \
+    char* base_ = lds + (buf) * STAGE_BYTES + st_off;                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                          \
+      *(u32x4*)(base_ + i * 64 * ROW_BYTES) = ra[i];                         \
+      *(u32x4*)(base_ + TILE_BYTES + i * 64 * ROW_BYTES) = rb[i];            \
+    }                                                                        \
+  }
 
   // ---- fragment addresses ---------------------------------------------------------
   // MFMA 32x32x16: lane l supplies row (l & 31) and the 8 k-values 8 (l >> 5) .. + 7 of A,
@@ -160,32 +160,80 @@ __global__ __launch_bounds__(THREADS) void gemm_bf16_kernel(KArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk = p.K / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const bool more = kt + 1 < nk;
-    if (more) load_global(kt + 1);
-    const char* st = lds + (kt & 1) * STAGE_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 a[4], b[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        a[i] = *(const bf16x8*)(st + a_frag + i * 32 * ROW_BYTES + kk * 32);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *(const bf16x8*)(st + b_frag[j] + kk * 32);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) store_lds((kt + 1) & 1);
-    __syncthreads();
+  // Fragment registers are double-buffered: while the 8 MFMAs of slice kk run, the reads of
+  // slice kk+1 are in flight.  Step kt of the K loop, with cur = kt & 1:
+  //   slices 0, 1: read next slice, MFMAs of this slice
+  //   slice 2: read slice 3, store tile kt+1 (already in registers) to the other LDS buffer,
+  //            issue the global loads of tile kt+2, then the MFMAs of slice 2 (they cover the
+  //            latency of the LDS stores)
+  //   barrier, read slice 0 of the other buffer, MFMAs of slice 3 (covering that read).
+  // One barrier per step: when it is reached every wavefront has read all of buffer cur and
+  // written its share of the other one.
+  bf16x8 fa[2][4], fb[2][2];
+#define MOEP_READ_FRAGS(buf, kk, slot)                                                        \
+  {                                                                                           \
+    const char* st_ = lds + (buf) * STAGE_BYTES + (kk) * 32;                                  \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                             \
+      fa[slot][i] = *(const bf16x8*)(st_ + a_frag + i * 32 * ROW_BYTES);                      \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                             \
+      fb[slot][j] = *(const bf16x8*)(st_ + b_frag[j]);                                        \
   }
+#define MOEP_MFMA(slot)                                                                       \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                             \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+// Scheduling hints: keep the order "MFMA, LDS read, MFMA, LDS read, ..." so that the reads of the
+// next slice are issued in the shadow of this slice's MFMAs instead of after them.
+#define MOEP_INTERLEAVE_READS()                                                               \
+  _Pragma("unroll") for (int q_ = 0; q_ < 6; ++q_) {                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                        \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
+  }                                                                                           \
+  __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#define MOEP_STEP(kt, HAS_NEXT, HAS_NEXT2)                                                    \
+  {                                                                                           \
+    const int cur_ = (kt) & 1;                                                                \
+    MOEP_READ_FRAGS(cur_, 1, 1)                                                               \
+    MOEP_MFMA(0)                                                                              \
+    MOEP_INTERLEAVE_READS()                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    MOEP_READ_FRAGS(cur_, 2, 0)                                                               \
+    MOEP_MFMA(1)                                                                              \
+    MOEP_INTERLEAVE_READS()                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    MOEP_READ_FRAGS(cur_, 3, 1)                                                               \
+    MOEP_MFMA(0)                                                                              \
+    MOEP_INTERLEAVE_READS()                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    if (HAS_NEXT) MOEP_STORE_LDS(cur_ ^ 1)                                                    \
+    if (HAS_NEXT2) { MOEP_LOAD_GLOBAL((kt) + 2) }                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    __syncthreads();                                                                          \
+    if (HAS_NEXT) MOEP_READ_FRAGS(cur_ ^ 1, 0, 0)                                             \
+    MOEP_MFMA(1)                                                                              \
+    if (HAS_NEXT) { MOEP_INTERLEAVE_READS() }                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+  }
+
+  const int nk = p.K / BK;
+  MOEP_LOAD_GLOBAL(0)
+  MOEP_STORE_LDS(0)
+  if (nk > 1) { MOEP_LOAD_GLOBAL(1) }
+  __syncthreads();
+  MOEP_READ_FRAGS(0, 0, 0)
+  int kt = 0;
+  for (; kt + 2 < nk; ++kt) MOEP_STEP(kt, true, true)
+  if (kt + 1 < nk) {
+    MOEP_STEP(kt, true, false)
+    ++kt;
+  }
+  MOEP_STEP(kt, false, false)
+#undef MOEP_LOAD_GLOBAL
+#undef MOEP_STORE_LDS
+#undef MOEP_READ_FRAGS
+#undef MOEP_MFMA
+#undef MOEP_STEP
+#undef MOEP_INTERLEAVE_READS
 
   // ---- epilogue ---------------------------------------------------------------------
   // Accumulator layout of a 32x32 tile: register v of lane l holds
@@ -238,7 +286,7 @@ int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name) {
   if (g.lda % 8 || g.ldc <= 0) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
   if (g.M <= 0 || g.N <= 0) return MOEP_OK;
   KArgs k;
-  k.A = (const uint4*)g.A; k.B0 = (const uint4*)g.B0; k.B1 = (const uint4*)g.B1;
+  k.A = (const u32x4*)g.A; k.B0 = (const u32x4*)g.B0; k.B1 = (const u32x4*)g.B1;
   k.a_rows = g.a_rows; k.C = g.C; k.row_scale = g.row_scale;
   k.tile_expert = g.tile_expert; k.tile_row0 = g.tile_row0; k.seg_end = g.seg_end;
   k.M = g.M; k.ldc = g.ldc;
