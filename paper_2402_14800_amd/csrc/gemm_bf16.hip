@@ -4,9 +4,13 @@
 // Tiling.  One workgroup of 512 threads (8 wavefronts, 2 along M x 4 along N) owns a
 // 256 x 256 tile of the accumulator and walks K in steps of 64.  Each wavefront owns a
 // 128 x 64 sub-tile = 4 x 2 MFMA tiles of 32 x 32 (128 accumulator registers per lane).
-// Operand tiles are staged through LDS (two buffers, one barrier per K step); rows are padded
-// from 128 to 144 bytes so that the 16-byte fragment reads of consecutive rows fall into
-// different banks.  Global loads for step i+1 are issued before the MFMAs of step i.
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging
+// registers, no LDS store instructions), two stages of 64 KB.  A direct load writes the 64 lanes'
+// 16-byte chunks to consecutive LDS addresses, so a stage is unpadded (128-byte rows) and bank
+// conflicts are avoided by permuting the chunks of each row: chunk c of tile row r is stored at
+// chunk position c ^ ((r ^ (r >> 3)) & 7), applied on the global side of the load (which chunk a
+// lane fetches) and undone in the fragment-read addresses.  Fragment registers are double-buffered;
+// the loads of tile kt+2 are issued right after the barrier that ends step kt.
 //
 // SwiGLU mode (the gate/up projection of one expert, Sec. 3.1): the 256 B-rows of a tile are
 // 128 rows of W1 followed by the SAME 128 rows of W3, and each wavefront's two N sub-tiles are
@@ -30,10 +34,10 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int THREADS = 512;
-constexpr int ROW_BYTES = 144;                 // 64 bf16 + 16 bytes of padding
+constexpr int ROW_BYTES = 128;                 // 64 bf16, unpadded (chunks are permuted instead)
 constexpr int TILE_BYTES = BM * ROW_BYTES;     // one operand tile (BM == BN)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // A tile then B tile
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;     // 147456
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;     // 131072
 static_assert(BM == GEMM_BM, "grouped tile maps are built for 256-row tiles");
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -96,60 +100,60 @@ void gemm_bf16_kernel(KArgs p) {
     row_end = p.M;
   }
 
-  // ---- global -> LDS staging: thread owns chunk column c of rows r0 + 64 i ---------
-  const int c = tid & 7;
-  const int r0 = tid >> 3;
+  // ---- global -> LDS direct loads ---------------------------------------------------
+  // Wavefront w fills tile rows 32 w .. 32 w + 31 of both operands: 4 loads per operand, each
+  // 8 rows x 8 chunks = 1 KB of LDS written contiguously in lane order.  Lane l lands on row
+  // (l >> 3), chunk position (l & 7) of its 8-row group and therefore fetches chunk
+  // (l & 7) ^ swz(row) of that row from global memory.
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   uint32_t a_off[4], b_off[4];
-  const u32x4* b_ptr[4];
+  const u32x4* b_base;
+  {
+    const int rr0 = wave_u * 32;                       // uniform: first tile row of this wavefront
+    if (EPI == EPI_SWIGLU) b_base = rr0 < 128 ? B0 : B1;   // rows 0..127 gate, 128..255 up
+    else b_base = B0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int64_t r = row0 + r0 + 64 * i;
-    if (r >= row_end) r = row_end - 1;               // tail rows re-read the last valid row
-    const int64_t src = p.a_rows ? (int64_t)p.a_rows[r] : r;
-    a_off[i] = (uint32_t)src * p.lda_chunks + c;
-    int n;
-    const u32x4* base;
-    if (EPI == EPI_SWIGLU) {
-      const int rr = r0 + 64 * i;                    // rows 0..127 gate, 128..255 up
-      n = tn * 128 + (rr & 127);
-      base = rr < 128 ? B0 : B1;
-    } else {
-      n = tn * BN + r0 + 64 * i;
-      base = B0;
+    for (int i = 0; i < 4; ++i) {
+      const int tr = rr0 + 8 * i + (lane >> 3);        // tile row
+      const int cch = (lane & 7) ^ ((tr ^ (tr >> 3)) & 7);
+      int64_t r = row0 + tr;
+      if (r >= row_end) r = row_end - 1;               // tail rows re-read the last valid row
+      const int64_t src = p.a_rows ? (int64_t)p.a_rows[r] : r;
+      a_off[i] = (uint32_t)src * p.lda_chunks + cch;
+      int n = EPI == EPI_SWIGLU ? tn * 128 + (tr & 127) : tn * BN + tr;
+      if (n >= p.N) n = p.N - 1;
+      b_off[i] = (uint32_t)n * p.ldb_chunks + cch;
     }
-    if (n >= p.N) n = p.N - 1;
-    b_ptr[i] = base;
-    b_off[i] = (uint32_t)n * p.ldb_chunks + c;
   }
-  const int st_off = r0 * ROW_BYTES + c * 16;        // + 64 i rows, + TILE_BYTES for B
-
-  u32x4 ra[4], rb[4];
-#define MOEP_LOAD_GLOBAL(kt)                                   \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {              \
-    ra[i] = p.A[a_off[i] + (uint32_t)(kt) * 8u];               \
-    rb[i] = b_ptr[i][b_off[i] + (uint32_t)(kt) * 8u];          \
-  }
-#define MOEP_STORE_LDS(buf)                                                  \
-  {                                                                          \
-    char* base_ = lds + (buf) * STAGE_BYTES + st_off;                        \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                          \
-      *(u32x4*)(base_ + i * 64 * ROW_BYTES) = ra[i];                         \
-      *(u32x4*)(base_ + TILE_BYTES + i * 64 * ROW_BYTES) = rb[i];            \
-    }                                                                        \
+  typedef __attribute__((address_space(3))) char lds_char;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  lds_char* const lds3 = (lds_char*)lds;
+#define MOEP_LOAD_TILE(kt, stage)                                                             \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                             \
+    __builtin_amdgcn_global_load_lds((gptr_t)(p.A + a_off[i] + (uint32_t)(kt) * 8u),          \
+        (__attribute__((address_space(3))) void*)(lds3 + (stage) * STAGE_BYTES +              \
+                                                  (wave_u * 32 + 8 * i) * ROW_BYTES), 16, 0, 0); \
+    __builtin_amdgcn_global_load_lds((gptr_t)(b_base + b_off[i] + (uint32_t)(kt) * 8u),       \
+        (__attribute__((address_space(3))) void*)(lds3 + (stage) * STAGE_BYTES + TILE_BYTES + \
+                                                  (wave_u * 32 + 8 * i) * ROW_BYTES), 16, 0, 0); \
   }
 
   // ---- fragment addresses ---------------------------------------------------------
   // MFMA 32x32x16: lane l supplies row (l & 31) and the 8 k-values 8 (l >> 5) .. + 7 of A,
-  // and the same for B (as [N,K]).  Per K step of 64 there are 4 such slices (kk).
+  // and the same for B (as [N,K]).  Per K step of 64 there are 4 such slices (kk): chunk
+  // 2 kk + (l >> 5) of the row, found at position chunk ^ swz(row); since swz only touches the
+  // chunk index, slice kk is at (address of slice 0) ^ (kk << 5).
   const int frow = lane & 31, fk = lane >> 5;
-  const int a_frag = (wm * 128 + frow) * ROW_BYTES + fk * 16;
-  int b_frag[2];
-  if (EPI == EPI_SWIGLU) {
-    b_frag[0] = TILE_BYTES + (wn * 32 + frow) * ROW_BYTES + fk * 16;
-    b_frag[1] = TILE_BYTES + (128 + wn * 32 + frow) * ROW_BYTES + fk * 16;
-  } else {
-    b_frag[0] = TILE_BYTES + (wn * 64 + frow) * ROW_BYTES + fk * 16;
-    b_frag[1] = TILE_BYTES + (wn * 64 + 32 + frow) * ROW_BYTES + fk * 16;
+  int a_frag[4], b_frag[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int tr = wm * 128 + i * 32 + frow;
+    a_frag[i] = tr * ROW_BYTES + ((fk ^ ((tr ^ (tr >> 3)) & 7)) << 4);
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int tr = EPI == EPI_SWIGLU ? j * 128 + wn * 32 + frow : wn * 64 + j * 32 + frow;
+    b_frag[j] = TILE_BYTES + tr * ROW_BYTES + ((fk ^ ((tr ^ (tr >> 3)) & 7)) << 4);
   }
 
   f32x16 acc[4][2];
@@ -160,36 +164,33 @@ void gemm_bf16_kernel(KArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // Fragment registers are double-buffered: while the 8 MFMAs of slice kk run, the reads of
-  // slice kk+1 are in flight.  Step kt of the K loop, with cur = kt & 1:
-  //   slices 0, 1: read next slice, MFMAs of this slice
-  //   slice 2: read slice 3, store tile kt+1 (already in registers) to the other LDS buffer,
-  //            issue the global loads of tile kt+2, then the MFMAs of slice 2 (they cover the
-  //            latency of the LDS stores)
-  //   barrier, read slice 0 of the other buffer, MFMAs of slice 3 (covering that read).
-  // One barrier per step: when it is reached every wavefront has read all of buffer cur and
-  // written its share of the other one.
+  // Step kt of the K loop works on stage cur = kt & 1:
+  //   slices 0..2: read next slice, MFMAs of this slice (reads issued in the MFMAs' shadow)
+  //   wait until this wavefront's loads of tile kt+1 have landed and its own reads are done,
+  //   barrier (now every wavefront has read all of stage cur and stage cur^1 is complete),
+  //   issue the loads of tile kt+2 into stage cur, read slice 0 of the other stage,
+  //   MFMAs of slice 3.
   bf16x8 fa[2][4], fb[2][2];
-#define MOEP_READ_FRAGS(buf, kk, slot)                                                        \
+#define MOEP_READ_FRAGS(stage, kk, slot)                                                      \
   {                                                                                           \
-    const char* st_ = lds + (buf) * STAGE_BYTES + (kk) * 32;                                  \
+    const char* st_ = lds + (stage) * STAGE_BYTES;                                            \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                             \
-      fa[slot][i] = *(const bf16x8*)(st_ + a_frag + i * 32 * ROW_BYTES);                      \
+      fa[slot][i] = *(const bf16x8*)(st_ + (a_frag[i] ^ ((kk) << 5)));                        \
     _Pragma("unroll") for (int j = 0; j < 2; ++j)                                             \
-      fb[slot][j] = *(const bf16x8*)(st_ + b_frag[j]);                                        \
+      fb[slot][j] = *(const bf16x8*)(st_ + (b_frag[j] ^ ((kk) << 5)));                        \
   }
 #define MOEP_MFMA(slot)                                                                       \
   _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
     _Pragma("unroll") for (int j = 0; j < 2; ++j)                                             \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
-// Scheduling hints: keep the order "MFMA, LDS read, MFMA, LDS read, ..." so that the reads of the
-// next slice are issued in the shadow of this slice's MFMAs instead of after them.
 #define MOEP_INTERLEAVE_READS()                                                               \
   _Pragma("unroll") for (int q_ = 0; q_ < 6; ++q_) {                                          \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                        \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
   }                                                                                           \
   __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+// s_waitcnt vmcnt(0) lgkmcnt(0): direct loads retire through vmcnt once their data is in LDS.
+#define MOEP_WAIT_ALL() __builtin_amdgcn_s_waitcnt(0x0070)
 #define MOEP_STEP(kt, HAS_NEXT, HAS_NEXT2)                                                    \
   {                                                                                           \
     const int cur_ = (kt) & 1;                                                                \
@@ -205,22 +206,23 @@ void gemm_bf16_kernel(KArgs p) {
     MOEP_MFMA(0)                                                                              \
     MOEP_INTERLEAVE_READS()                                                                   \
     __builtin_amdgcn_sched_barrier(0);                                                        \
-    if (HAS_NEXT) MOEP_STORE_LDS(cur_ ^ 1)                                                    \
-    if (HAS_NEXT2) { MOEP_LOAD_GLOBAL((kt) + 2) }                                             \
+    MOEP_WAIT_ALL();                                                                          \
+    __builtin_amdgcn_s_barrier();                                                             \
     __builtin_amdgcn_sched_barrier(0);                                                        \
-    __syncthreads();                                                                          \
+    if (HAS_NEXT2) { MOEP_LOAD_TILE((kt) + 2, cur_) }                                         \
     if (HAS_NEXT) MOEP_READ_FRAGS(cur_ ^ 1, 0, 0)                                             \
     MOEP_MFMA(1)                                                                              \
-    if (HAS_NEXT) { MOEP_INTERLEAVE_READS() }                                                 \
     __builtin_amdgcn_sched_barrier(0);                                                        \
   }
 
   const int nk = p.K / BK;
-  MOEP_LOAD_GLOBAL(0)
-  MOEP_STORE_LDS(0)
-  if (nk > 1) { MOEP_LOAD_GLOBAL(1) }
-  __syncthreads();
+  MOEP_LOAD_TILE(0, 0)
+  MOEP_WAIT_ALL();
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  if (nk > 1) { MOEP_LOAD_TILE(1, 1) }
   MOEP_READ_FRAGS(0, 0, 0)
+  __builtin_amdgcn_sched_barrier(0);
   int kt = 0;
   for (; kt + 2 < nk; ++kt) MOEP_STEP(kt, true, true)
   if (kt + 1 < nk) {
@@ -228,12 +230,12 @@ void gemm_bf16_kernel(KArgs p) {
     ++kt;
   }
   MOEP_STEP(kt, false, false)
-#undef MOEP_LOAD_GLOBAL
-#undef MOEP_STORE_LDS
+#undef MOEP_LOAD_TILE
 #undef MOEP_READ_FRAGS
 #undef MOEP_MFMA
 #undef MOEP_STEP
 #undef MOEP_INTERLEAVE_READS
+#undef MOEP_WAIT_ALL
 
   // ---- epilogue ---------------------------------------------------------------------
   // Accumulator layout of a 32x32 tile: register v of lane l holds
