@@ -234,3 +234,135 @@ def test_skip_empty_batch_and_bad_k():
     with pytest.raises(pkg.MoepError) as ei:
         pkg.moe_forward_skip(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"], 0.5, k=3)
     assert ei.value.status == 2
+
+
+# ================================================================== full-size configurations
+# The launch shapes bench.py times.  The oracle cannot redo these sizes in seconds, so outputs are
+# checked on sampled tokens (each expert output row is computable on its own) and the summed losses
+# through a token prefix plus properties that hold at any size (additivity over token ranges, the
+# count of unaffected pairs, reproducibility).
+
+def sampled_expert_check(layer, logits_t, Y_t, tokens, W64):
+    x64 = wl.to_f64(layer["x"][tokens])
+    ref_logits, ref_Y = oracle.expert_outputs(x64, wl.to_f64(layer["Wgate"]), W64["W1"], W64["W3"], W64["W2"])
+    got_logits = logits_t[tokens].cpu().numpy().astype(np.float64)
+    assert np.abs(got_logits - ref_logits).max() <= 1e-3 * np.abs(ref_logits).max()
+    check_outputs(wl.to_f64(Y_t[:, tokens]), ref_Y, "Y (sampled tokens)")
+
+
+def weights_f64(layer):
+    return {n: [wl.to_f64(layer[n][e]) for e in range(layer[n].shape[0])] for n in ("W1", "W3", "W2")}
+
+
+def test_config2_full_size():
+    cfg = wl.CONFIGS["C2"]
+    layer = wl.make_layer(cfg, device=DEV)
+    x, Wg, W1, W3, W2 = (layer[n] for n in ("x", "Wgate", "W1", "W3", "W2"))
+    logits_t, Y_t = pkg.moe_expert_outputs(x, Wg, W1, W3, W2)
+    torch.cuda.synchronize()
+    tokens = torch.tensor(np.random.default_rng(2).choice(cfg.T, 256, replace=False), device=DEV).sort().values
+    sampled_expert_check(layer, logits_t, Y_t, tokens, weights_f64(layer))
+    for r in cfg.rs:
+        loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, cfg.k, r)
+        ref, _, masks = oracle.prune_enumerate_streamed(logits_t, Y_t, cfg.k, r, chunk=4096, to_f64=wl.to_f64)
+        check_losses(loss, ref)
+        check_argmin(amin, ref, loss)
+        assert amask == int(masks[amin])
+        assert unaff == cfg.T * math.comb(cfg.E - cfg.k, r - cfg.k)
+
+
+@pytest.fixture(scope="module")
+def config3():
+    cfg = wl.CONFIGS["C3"]
+    layer = wl.make_layer(cfg, device=DEV)
+    x, Wg, W1, W3, W2 = (layer[n] for n in ("x", "Wgate", "W1", "W3", "W2"))
+    logits_t, Y_t = pkg.moe_expert_outputs(x, Wg, W1, W3, W2)
+    torch.cuda.synchronize()
+    yield cfg, layer, logits_t, Y_t, weights_f64(layer)
+    del layer, logits_t, Y_t
+    torch.cuda.empty_cache()
+
+
+def test_config3_expert_outputs_sampled(config3):
+    cfg, layer, logits_t, Y_t, W64 = config3
+    rng_ = np.random.default_rng(3)
+    # a few tokens from the first and last M tile plus random ones
+    tokens = np.unique(np.concatenate([[0, 255, 256, cfg.T - 257, cfg.T - 1], rng_.choice(cfg.T, 43, replace=False)]))
+    sampled_expert_check(layer, logits_t, Y_t, torch.tensor(tokens, device=DEV), W64)
+
+
+def test_config3_enumeration(config3):
+    cfg, layer, logits_t, Y_t, _ = config3
+    T, half, prefix = cfg.T, cfg.T // 2 + 1024, 4096
+    for r in cfg.rs:
+        loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, cfg.k, r)
+        assert unaff == T * math.comb(cfg.E - cfg.k, r - cfg.k)
+        assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(cfg.E, r, amin)
+        # additivity over a ragged split of the tokens (same kernels, different tilings)
+        la, _, _, ua = run_enumerate(logits_t[:half].contiguous(), Y_t[:, :half].contiguous(), cfg.k, r)
+        lb, _, _, ub = run_enumerate(logits_t[half:].contiguous(), Y_t[:, half:].contiguous(), cfg.k, r)
+        np.testing.assert_allclose(la + lb, loss, rtol=2e-5)
+        assert ua + ub == unaff
+        # the oracle on a token prefix
+        lp, ap, _, _ = run_enumerate(logits_t[:prefix].contiguous(), Y_t[:, :prefix].contiguous(), cfg.k, r)
+        ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[:prefix]), wl.to_f64(Y_t[:, :prefix]), cfg.k, r)
+        check_losses(lp, ref)
+        check_argmin(ap, ref, lp)
+        # reproducible bit for bit
+        loss2, amin2, _, _ = run_enumerate(logits_t, Y_t, cfg.k, r)
+        assert np.array_equal(loss, loss2) and amin == amin2
+
+
+def test_config5_skip_forward_sampled(config3):
+    cfg, layer, _, _, W64 = config3
+    Ts = wl.CONFIGS["C5"].T
+    x = layer["x"][:Ts]
+    Wg, W1, W3, W2 = (layer[n] for n in ("Wgate", "W1", "W3", "W2"))
+    _, _, lg, _ = pkg.moe_forward_skip(x, Wg, W1, W3, W2, 0.0)
+    torch.cuda.synchronize()
+    beta = float(np.float32(oracle.median_skip_ratio(lg.cpu().numpy())))
+    out_t, skip_t, logits_t, top2_t = pkg.moe_forward_skip(x, Wg, W1, W3, W2, beta)
+    torch.cuda.synchronize()
+    assert torch.equal(logits_t, lg)
+    # decisions: every token, exactly
+    e0, e1, ref_skip, _ = oracle.skip_decision(logits_t.cpu().numpy(), beta)
+    assert np.array_equal(skip_t.cpu().numpy().astype(bool), ref_skip)
+    top2 = top2_t.cpu().numpy()
+    assert np.array_equal(top2[:, 0], e0) and np.array_equal(top2[:, 1], e1)
+    assert abs(ref_skip.mean() - 0.5) <= 1.0 / Ts + 1e-9
+    # outputs: sampled tokens through the fp64 experts
+    tokens = np.unique(np.concatenate([[0, Ts - 1], np.random.default_rng(5).choice(Ts, 46, replace=False)]))
+    tt = torch.tensor(tokens, device=DEV)
+    ref_out, rs, _, _ = oracle.forward_skip(wl.to_f64(x[tt]), wl.to_f64(Wg), W64["W1"], W64["W3"], W64["W2"], beta,
+                                            logits=logits_t[tt].cpu().numpy())
+    assert np.array_equal(rs, ref_skip[tokens])
+    check_outputs(wl.to_f64(out_t[tt]), ref_out, "skip out (sampled tokens)")
+    # never skipping reproduces Eq. 2 on the dense expert outputs
+    out0, skip0, _, _ = pkg.moe_forward_skip(x, Wg, W1, W3, W2, 0.0)
+    torch.cuda.synchronize()
+    assert int(skip0.sum().item()) == 0
+
+
+def test_config4_enumeration_stress():
+    cfg = wl.CONFIGS["C4"]
+    E, k, H, T = cfg.E, cfg.k, cfg.H, cfg.T
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(cfg.seed)
+    bias = torch.randn((E,), generator=gen, device=DEV) * cfg.gate_bias_var ** 0.5
+    logits_t = torch.randn((T, E), generator=gen, device=DEV) + bias
+    Y_t = torch.randn((E, T, H), generator=gen, device=DEV).to(torch.bfloat16)
+    load = torch.bincount(torch.topk(logits_t, k, dim=1).indices.flatten(), minlength=E).float()
+    assert load.max() > 1.5 * load.min()                     # experts are unequally used
+    for r, prefix in ((12, 1024), (8, 384)):
+        loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, k, r)
+        assert len(loss) == math.comb(E, r)
+        assert unaff == T * math.comb(E - k, r - k)
+        assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(E, r, amin)
+        cut = T // 3 + 7
+        la, _, _, _ = run_enumerate(logits_t[:cut].contiguous(), Y_t[:, :cut].contiguous(), k, r)
+        lb, _, _, _ = run_enumerate(logits_t[cut:].contiguous(), Y_t[:, cut:].contiguous(), k, r)
+        np.testing.assert_allclose(la + lb, loss, rtol=2e-5)
+        lp, ap, _, _ = run_enumerate(logits_t[:prefix].contiguous(), Y_t[:, :prefix].contiguous(), k, r)
+        ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[:prefix]), wl.to_f64(Y_t[:, :prefix]), k, r)
+        check_losses(lp, ref)
+        check_argmin(ap, ref, lp)
