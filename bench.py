@@ -29,9 +29,11 @@ if ROOT not in sys.path:
 PEAK_MFMA_BF16_TFLOPS = 2500.0     # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
-# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"C3": None, "C2": None}
+# Fabric-side traffic per launch of the dominant kernel (dense gate/up GEMM) measured with
+# rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs of this script with --copy-calibration, each
+# scaled by what the 1 GiB copy reads on the same counter: x2.000 and x1.000); the figures are in
+# profiles/hot_path_C3_hbm_traffic.txt.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {"C3": 97.7e9, "C2": None}
 
 
 def parse():
