@@ -110,6 +110,20 @@ int moe_forward_skip(const void* x, const void* Wgate, const void* W1, const voi
                      float beta, void* out, uint8_t* skip_mask, float* logits_out,
                      int32_t* top2_out, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- moe_forward_pruned_skip ---------------------------------------------- */
+/* The deployable layer after pruning (Sec. 3.2: the experts outside the kept set C and their
+ * routing weights are removed), optionally with dynamic skipping on top (Sec. 3.3: the two can be
+ * used together).  Exactly moe_forward_skip, except that the top-2 experts are taken among the
+ * experts whose bit is set in `kept_mask` (bit e = expert e; at least two bits below bit E).
+ * With beta = 0 the output is F'(x, C) of Sec. 3.2; with every bit set it is moe_forward_skip.
+ * Weights and logits keep their original expert indexing; removed experts are simply never
+ * routed to.  Workspace: moe_forward_skip_workspace. */
+int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
+                            const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                            uint32_t kept_mask, float beta, void* out, uint8_t* skip_mask,
+                            float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
+                            void* hip_stream);
+
 /* ---- per-kernel timing (for benchmarks) ------------------------------------ */
 /* While enabled, every kernel launch is bracketed by HIP events on its stream.
  * moep_timing_collect waits for the recorded events, adds them up per kernel and

@@ -178,8 +178,13 @@ def prune_enumerate_streamed(logits, Y, k: int, r: int, chunk: int = 8192, to_f6
 # --------------------------------------------------------------------------- #
 # Sec. 3.3 / App. A.2: dynamic skipping, top-2
 # --------------------------------------------------------------------------- #
-def skip_decision(logits: np.ndarray, beta: float):
+def skip_decision(logits: np.ndarray, beta: float, kept=None):
     """Top-2 experts and the rule of Sec. 3.3: skip e1 iff w_e1 < beta * w_e0.
+
+    With `kept` (an iterable of expert indices, at least two) the layer is the pruned
+    one of Sec. 3.2 -- the other experts and their routing weights are gone -- and
+    the top-2 are taken among the kept experts; Sec. 3.3 notes that skipping and
+    pruning can be used together.
 
     w_e1 / w_e0 = exp(l_e1 - l_e0) whichever softmax the weights came from, so the
     rule is l_e1 - l_e0 < ln(beta).  This is the one place where floating point
@@ -192,29 +197,40 @@ def skip_decision(logits: np.ndarray, beta: float):
     """
     l32 = np.asarray(logits, dtype=np.float32)
     order = routing_order(l32)
-    e0, e1 = order[:, 0], order[:, 1]
     t = np.arange(l32.shape[0])
+    if kept is None:
+        e0, e1 = order[:, 0], order[:, 1]
+    else:
+        allowed = np.zeros(l32.shape[1], dtype=bool)
+        allowed[list(kept)] = True
+        if allowed.sum() < 2:
+            raise ValueError("top-2 routing needs at least two kept experts")
+        flags = allowed[order]                            # rank order
+        nth = np.cumsum(flags, axis=1)
+        e0 = order[t, np.argmax(flags & (nth == 1), axis=1)]
+        e1 = order[t, np.argmax(flags & (nth == 2), axis=1)]
     delta = (l32[t, e1] - l32[t, e0]).astype(np.float32)
     b = float(np.float32(beta))
     theta = np.float32(-np.inf) if b <= 0.0 else np.float32(math.log(b))
     return e0, e1, delta < theta, delta
 
 
-def forward_skip(x, Wgate, W1, W3, W2, beta: float, logits=None):
+def forward_skip(x, Wgate, W1, W3, W2, beta: float, logits=None, kept=None):
     """The MoE forward with dynamic skipping, k = 2 (Sec. 3.3; output per App. A.2).
 
     Tokens that skip keep only e0 and renormalise over the survivors, i.e.
     out = E_{e0}(x); the others get Eq. 2.  Only the routed (token, expert) pairs
     are pushed through an expert.  If `logits` is given it replaces x Wgate^T
     (so that the decision can be checked on the very logits another
-    implementation produced).
+    implementation produced).  `kept` restricts the layer to a kept set of experts
+    (the pruned layer F'(x, C) of Sec. 3.2, here with k = 2).
 
     Returns out [T,H], skip [T] bool, e0 [T], e1 [T].
     """
     x = np.asarray(x, dtype=np.float64)
     if logits is None:
         logits = x @ np.asarray(Wgate, dtype=np.float64).T
-    e0, e1, skip, _ = skip_decision(logits, beta)
+    e0, e1, skip, _ = skip_decision(logits, beta, kept)
     l64 = np.asarray(logits, dtype=np.float64)
     t = np.arange(x.shape[0])
     rho = np.exp(l64[t, e1] - l64[t, e0])                 # w_e1 / w_e0

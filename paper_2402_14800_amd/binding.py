@@ -24,7 +24,7 @@ EXPORTS = (
     "moep_num_subsets", "moep_subset_unrank", "moep_subset_rank", "moep_last_error",
     "moe_expert_outputs_workspace", "moe_expert_outputs",
     "prune_enumerate_workspace", "prune_enumerate",
-    "moe_forward_skip_workspace", "moe_forward_skip",
+    "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moep_timing_enable", "moep_timing_collect",
 )
 
@@ -69,6 +69,10 @@ def _load() -> ctypes.CDLL:
     lib.moe_forward_skip.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_float,
                                                       c_void_p, c_void_p, c_void_p, c_void_p,
                                                       c_void_p, c_size_t, c_void_p]
+    lib.moe_forward_pruned_skip.restype = c_int
+    lib.moe_forward_pruned_skip.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_uint32,
+                                                             c_float, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                             c_void_p, c_size_t, c_void_p]
     lib.moep_timing_enable.restype = c_int
     lib.moep_timing_enable.argtypes = [c_int]
     lib.moep_timing_collect.restype = c_int
@@ -187,8 +191,9 @@ def moe_forward_skip_workspace(T: int, E: int, H: int, F: int, dtype_code: int) 
 
 
 def moe_forward_skip(x, Wgate, W1, W3, W2, beta: float, k: int = 2, workspace=None,
-                     want_logits: bool = True, want_top2: bool = True):
-    """out [T,H], skip_mask [T] uint8, logits [T,E] fp32 (or None), top2 [T,2] int32 (or None)."""
+                     want_logits: bool = True, want_top2: bool = True, kept_mask: Optional[int] = None):
+    """out [T,H], skip_mask [T] uint8, logits [T,E] fp32 (or None), top2 [T,2] int32 (or None).
+    With `kept_mask` the call goes to moe_forward_pruned_skip (top-2 among the kept experts)."""
     dev = _dev(x, Wgate, W1, W3, W2)
     dt = _dtype_code(x)
     T, H = x.shape
@@ -200,10 +205,19 @@ def moe_forward_skip(x, Wgate, W1, W3, W2, beta: float, k: int = 2, workspace=No
     top2 = torch.empty((T, 2), dtype=torch.int32, device=dev) if want_top2 else None
     need = _lib.moe_forward_skip_workspace(T, E, H, F, dt)
     ws = _workspace(need, dev, workspace)
-    _check(_lib.moe_forward_skip(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt, k,
-                                 c_float(beta), _ptr(out), _ptr(skip), _ptr(logits), _ptr(top2),
-                                 _ptr(ws), ws.numel(), _stream(dev)))
+    if kept_mask is None:
+        _check(_lib.moe_forward_skip(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt, k,
+                                     c_float(beta), _ptr(out), _ptr(skip), _ptr(logits), _ptr(top2),
+                                     _ptr(ws), ws.numel(), _stream(dev)))
+    else:
+        _check(_lib.moe_forward_pruned_skip(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt, k,
+                                            c_uint32(kept_mask), c_float(beta), _ptr(out), _ptr(skip),
+                                            _ptr(logits), _ptr(top2), _ptr(ws), ws.numel(), _stream(dev)))
     return out, skip, logits, top2
+
+
+def moe_forward_pruned_skip(x, Wgate, W1, W3, W2, kept_mask: int, beta: float, **kw):
+    return moe_forward_skip(x, Wgate, W1, W3, W2, beta, kept_mask=kept_mask, **kw)
 
 
 # ---------------------------------------------------------------- kernel timing

@@ -264,10 +264,22 @@ int moe_forward_skip(const void* x, const void* Wgate, const void* W1, const voi
                      const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
                      float beta, void* out, uint8_t* skip_mask, float* logits_out,
                      int32_t* top2_out, void* ws, size_t ws_bytes, void* hip_stream) {
+  const uint32_t all = (E >= 1 && E < 32) ? (1u << E) - 1u : 0xffffffffu;
+  return moe_forward_pruned_skip(x, Wgate, W1, W3, W2, T, E, H, F, dt, k, all, beta, out, skip_mask,
+                                 logits_out, top2_out, ws, ws_bytes, hip_stream);
+}
+
+int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
+                            const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                            uint32_t kept_mask, float beta, void* out, uint8_t* skip_mask,
+                            float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
+                            void* hip_stream) {
   const char* who = "moe_forward_skip";
   if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
   if (k != 2) return fail(MOEP_EUNSUPPORTED, "%s: only k = 2 is implemented (k=%d)", who, k);
   if (E < 2) return fail(MOEP_EINVAL, "%s: top-2 routing needs E >= 2 (E=%d)", who, E);
+  if (E < 32 && (kept_mask >> E)) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x has bits beyond expert %d", who, kept_mask, E - 1);
+  if (__builtin_popcount(kept_mask) < 2) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x keeps fewer than two experts", who, kept_mask);
   if (!(beta >= 0.0f) || std::isinf(beta)) return fail(MOEP_EINVAL, "%s: beta must be finite and >= 0", who);
   if (int st = check_alignment(H, F, dt, who)) return st;
   if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
@@ -282,7 +294,7 @@ int moe_forward_skip(const void* x, const void* Wgate, const void* W1, const voi
 
   float* logits = logits_out ? logits_out : (float*)(w + p.off_logits);
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
-  if (int st = launch_skip_routing(p, logits, beta, skip_mask, top2_out, w, s)) return st;
+  if (int st = launch_skip_routing(p, logits, kept_mask, beta, skip_mask, top2_out, w, s)) return st;
 
   GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
   up.A = x; up.lda = H; up.a_rows = (const int32_t*)(w + p.off_slot_token);

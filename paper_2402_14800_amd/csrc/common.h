@@ -98,7 +98,7 @@ struct SkipPlan {
          off_tile_expert, off_tile_row0, off_h, off_slot_out, total;
 };
 int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, SkipPlan* p);
-int launch_skip_routing(const SkipPlan& p, const float* logits, float beta, uint8_t* skip_mask,
+int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,
                         int32_t* top2_out, char* ws, hipStream_t s);
 int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
                         char* ws, hipStream_t s);

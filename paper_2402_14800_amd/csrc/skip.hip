@@ -1,7 +1,7 @@
 // Dynamic skipping, top-2 (Sec. 3.3; output per App. A.2): routing, dispatch and combine.
 // The expert FFNs themselves are the grouped GEMMs (see gemm_bf16.hip / gemm_f32.hip).
 //
-//   route    per token: top-2 experts by logit (ties -> lower index), delta = l_e1 - l_e0 in fp32,
+//   route    per token: top-2 experts by logit among the kept experts (ties -> lower index), delta = l_e1 - l_e0 in fp32,
 //            skip iff delta < theta = fp32(ln beta) (theta = -inf for beta = 0), weights
 //            a0 = 1 / (1 + rho), a1 = rho / (1 + rho), rho = exp(delta); a0 = 1 when skipped.
 //            Also counts, per block of 256 tokens, the rows each expert receives.
@@ -21,7 +21,7 @@ namespace {
 constexpr int RB = 256;     // tokens per routing block
 
 __global__ __launch_bounds__(RB) void route_kernel(const float* __restrict__ logits, int64_t T,
-                                                   int E, float theta, uint8_t* __restrict__ skip_mask,
+                                                   int E, uint32_t kept, float theta, uint8_t* __restrict__ skip_mask,
                                                    int32_t* __restrict__ top2,
                                                    float* __restrict__ tw, int32_t* __restrict__ counts) {
   __shared__ int cnt[32];
@@ -30,11 +30,12 @@ __global__ __launch_bounds__(RB) void route_kernel(const float* __restrict__ log
   const int64_t t = (int64_t)blockIdx.x * RB + threadIdx.x;
   if (t < T) {
     const float* l = logits + t * E;
-    int e0 = 0, e1 = -1;
-    float l0 = l[0], l1 = -INFINITY;
-    for (int e = 1; e < E; ++e) {          // strict comparisons: the lower index wins a tie
+    int e0 = -1, e1 = -1;
+    float l0 = -INFINITY, l1 = -INFINITY;
+    for (int e = 0; e < E; ++e) {          // strict comparisons: the lower index wins a tie
+      if (!((kept >> e) & 1u)) continue;   // a removed expert and its routing weight are gone
       const float v = l[e];
-      if (v > l0) { l1 = l0; e1 = e0; l0 = v; e0 = e; }
+      if (e0 < 0 || v > l0) { l1 = l0; e1 = e0; l0 = v; e0 = e; }
       else if (e1 < 0 || v > l1) { l1 = v; e1 = e; }
     }
     const float delta = l1 - l0;
@@ -190,7 +191,7 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, SkipPlan* p) {
   return MOEP_OK;
 }
 
-int launch_skip_routing(const SkipPlan& p, const float* logits, float beta, uint8_t* skip_mask,
+int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,
                         int32_t* top2_out, char* ws, hipStream_t s) {
   const int64_t T = p.T;
   int32_t* pos = (int32_t*)(ws + p.off_pos);
@@ -200,7 +201,7 @@ int launch_skip_routing(const SkipPlan& p, const float* logits, float beta, uint
   const int64_t n_blocks = ceil_div(T, RB);
   const float theta = beta > 0.0f ? (float)std::log((double)beta) : -INFINITY;
   Timed t("skip_route_dispatch", s);
-  hipLaunchKernelGGL(route_kernel, dim3((unsigned)n_blocks), dim3(RB), 0, s, logits, T, p.E, theta,
+  hipLaunchKernelGGL(route_kernel, dim3((unsigned)n_blocks), dim3(RB), 0, s, logits, T, p.E, kept_mask, theta,
                      skip_mask, top2, tw, counts);
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, counts, n_blocks, p.E,
                      (int32_t*)(ws + p.off_seg_end), (int32_t*)(ws + p.off_tile_expert),

@@ -366,3 +366,39 @@ def test_config4_enumeration_stress():
         ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[:prefix]), wl.to_f64(Y_t[:, :prefix]), k, r)
         check_losses(lp, ref)
         check_argmin(ap, ref, lp)
+
+
+# ------------------------------------------------------------------ pruned + skipping forward
+@pytest.mark.parametrize("dtype,E,H,F,T,r", [("bf16", 8, 256, 512, 900, 6), ("f32", 6, 64, 128, 300, 3),
+                                             ("bf16", 8, 128, 256, 500, 2)])
+def test_pruned_skip_forward_matches_oracle_and_enumeration(dtype, E, H, F, T, r):
+    cfg, layer = small_layer(dtype, E, 2, H, F, T, index=11)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    logits_t, Y_t = pkg.moe_expert_outputs(*ws)
+    loss, amin, amask, _ = run_enumerate(logits_t, Y_t, 2, r)
+    kept = [e for e in range(E) if (amask >> e) & 1]
+    args = [wl.to_f64(layer[n]) for n in ("x", "Wgate", "W1", "W3", "W2")]
+    for beta in (0.0, float(np.float32(0.5))):
+        out_t, skip_t, lg, top2_t = pkg.moe_forward_pruned_skip(*ws, amask, beta)
+        torch.cuda.synchronize()
+        assert torch.equal(lg, logits_t)
+        ref_out, ref_skip, e0, e1 = oracle.forward_skip(*args, beta, logits=lg.cpu().numpy(), kept=kept)
+        assert np.array_equal(skip_t.cpu().numpy().astype(bool), ref_skip)
+        top2 = top2_t.cpu().numpy()
+        assert np.array_equal(top2[:, 0], e0) and np.array_equal(top2[:, 1], e1)
+        assert set(np.unique(top2)) <= set(kept)
+        check_outputs(wl.to_f64(out_t), ref_out, "pruned out")
+    # beta = 0: the pruned forward is F'(x, C); its distance to the full forward is the Eq. 3 loss
+    # the enumeration reported for that subset (different kernels: GEMMs on routed rows vs Gram).
+    pruned, _, _, _ = pkg.moe_forward_pruned_skip(*ws, amask, 0.0)
+    full, _, _, _ = pkg.moe_forward_skip(*ws, 0.0)
+    torch.cuda.synchronize()
+    dist = float(((pruned.double() - full.double()) ** 2).sum().item())
+    assert dist == pytest.approx(loss[amin], rel=3e-2)
+    allmask = (1 << E) - 1
+    same, sk2, _, _ = pkg.moe_forward_pruned_skip(*ws, allmask, 0.5)
+    ref2, sk1, _, _ = pkg.moe_forward_skip(*ws, 0.5)
+    torch.cuda.synchronize()
+    assert torch.equal(same.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       ref2.view(torch.int16 if dtype == "bf16" else torch.int32)) and torch.equal(sk1, sk2)

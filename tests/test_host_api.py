@@ -102,6 +102,11 @@ def test_argument_errors_come_back_as_status_codes():
     assert f(*args(beta=float("nan"))) == 1
     assert f(*args(E=1)) == 1
     assert f(*args(H=100)) == 2
+    fp = binding._lib.moe_forward_pruned_skip
+    pargs = lambda mask, **kw: (lambda a: a[:11] + [ctypes.c_uint32(mask)] + a[11:])(args(**kw))
+    assert fp(*pargs(0b1)) == 1                   # fewer than two kept experts
+    assert fp(*pargs(0b1_0000_0011)) == 1         # bit beyond E = 8
+    assert fp(*pargs(0b11, k=3)) == 2
     g = binding._lib.moe_expert_outputs
     gargs = lambda **kw: [one] * 5 + [kw.get("T", 64), kw.get("E", 8), kw.get("H", 64), kw.get("F", 128),
                                       kw.get("dt", 1), one, one, one, kw.get("ws", 1 << 40), None]

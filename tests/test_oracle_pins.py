@@ -352,3 +352,27 @@ def test_skip_uses_given_logits():
     assert np.all(e0 == 3) and np.all(e1 == 1)
     assert skip.all()                      # exp(-1) = 0.37 < 0.5
     np.testing.assert_allclose(out, oracle.expert_ffn(x, W1[3], W3[3], W2[3]), rtol=1e-12)
+
+
+def test_pruned_skip_forward_reduces_to_known_cases():
+    # kept = everything is the unpruned forward; with beta = 0 the pruned forward is F'(x, C) of
+    # Sec. 3.2 (computed by the enumeration code path), so its distance to the full layer is Eq. 3.
+    x, Wg, W1, W3, W2 = skip_case(15, T=40, E=6)
+    logits, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    a = oracle.forward_skip(x, Wg, W1, W3, W2, 0.55)
+    b = oracle.forward_skip(x, Wg, W1, W3, W2, 0.55, kept=range(6))
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    kept = (0, 2, 3, 5)
+    out, skip, e0, e1 = oracle.forward_skip(x, Wg, W1, W3, W2, 0.0, kept=kept)
+    assert not skip.any() and set(e0) | set(e1) <= set(kept)
+    np.testing.assert_allclose(out, oracle.pruned_layer_output(logits, Y, kept, 2), rtol=1e-11, atol=1e-13)
+    loss, _, _ = oracle.prune_enumerate(logits, Y, 2, 4)
+    idx = oracle.kept_subsets(6, 4).index(kept)
+    full, _, _, _ = oracle.forward_skip(x, Wg, W1, W3, W2, 0.0)
+    assert float(np.sum((out - full) ** 2)) == pytest.approx(loss[idx], rel=1e-10)
+    # ties and order: the two best KEPT experts, lower index first on equal logits
+    forced = np.tile(np.array([[3.0, 1.0, 3.0, 2.0, 2.0, 0.0]], dtype=np.float32), (40, 1))
+    _, _, e0, e1 = oracle.forward_skip(x, Wg, W1, W3, W2, 0.0, logits=forced, kept=(1, 3, 4, 5))
+    assert np.all(e0 == 3) and np.all(e1 == 4)
+    with pytest.raises(ValueError):
+        oracle.skip_decision(forced, 0.5, kept=(2,))
