@@ -227,13 +227,16 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ log
 }
 
 // ------------------------------------------------------------------ scoring
-template <int CAP>
+// EXACT: every one of the CAP rank positions is in use (n_act == CAP), which removes the
+// per-position guards from the token loop.
+template <int CAP, bool EXACT>
 __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ rec, int64_t T,
                                                     int tok_tile, int E, int r, int kk, int kfull,
-                                                    int n_act, uint32_t n_sub,
+                                                    int n_act_rt, uint32_t n_sub,
                                                     float* __restrict__ partial,
                                                     uint32_t* __restrict__ partial_cnt) {
   constexpr int RS = rec_size(CAP);
+  const int n_act = EXACT ? CAP : n_act_rt;
   constexpr int OFF_L = CAP, OFF_A = 2 * CAP, OFF_G = 3 * CAP, OFF_O = rec_order_off(CAP);
   const uint32_t sub = blockIdx.x * blockDim.x + threadIdx.x;
   const bool live = sub < n_sub;
@@ -248,6 +251,14 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
   for (int64_t t = t_begin; t < t_end; ++t) {
     const float* R = rec + t * RS;                       // wave-uniform
     const uint32_t* Rord = (const uint32_t*)(R + OFF_O);
+    // Everything the selection needs is fetched up front, unconditionally (wave-uniform scalar
+    // loads), so that no load sits behind a lane-dependent condition.
+    float ex[CAP], aw[CAP];
+    uint32_t ordw[(CAP + 3) / 4];
+#pragma unroll
+    for (int j = 0; j < CAP; ++j) { ex[j] = R[j]; aw[j] = R[OFF_A + j]; }
+#pragma unroll
+    for (int j = 0; j < (CAP + 3) / 4; ++j) ordw[j] = Rord[j];
     float w[CAP];
     float sum = 0.f;
     uint32_t bits = 0;
@@ -256,11 +267,11 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
     for (int j = 0; j < CAP; ++j) {
       w[j] = 0.f;
       if (j < n_act) {
-        const uint32_t e = (Rord[j >> 2] >> (8 * (j & 3))) & 0xffu;
+        const uint32_t e = (ordw[j >> 2] >> (8 * (j & 3))) & 0xffu;
         const bool take = ((mask >> e) & 1u) && cnt < kk;
         cnt += take ? 1 : 0;
         bits |= take ? (1u << j) : 0u;
-        w[j] = take ? R[j] : 0.f;
+        w[j] = take ? ex[j] : 0.f;
         sum += w[j];
       }
     }
@@ -282,7 +293,7 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
     const float inv = __builtin_amdgcn_rcpf(sum);
     float d[CAP];
 #pragma unroll
-    for (int j = 0; j < CAP; ++j) d[j] = fmaf(w[j], inv, -R[OFF_A + j]);
+    for (int j = 0; j < CAP; ++j) d[j] = fmaf(w[j], inv, -aw[j]);
     float q = 0.f;
     int gi = OFF_G;
 #pragma unroll
@@ -414,8 +425,12 @@ static void launch_score(const EnumPlan& p, const float* rec, float* partial, ui
                          hipStream_t s) {
   const int threads = p.n_sub <= 64 ? 64 : 256;
   dim3 grid((unsigned)ceil_div(p.n_sub, threads), (unsigned)p.n_tok_tiles);
-  hipLaunchKernelGGL(score_kernel<CAP>, grid, dim3(threads), 0, s, rec, p.T, p.tok_tile, p.E, p.r,
-                     p.kk, p.k, p.n_act, (uint32_t)p.n_sub, partial, pcnt);
+  if (p.n_act == CAP)
+    hipLaunchKernelGGL((score_kernel<CAP, true>), grid, dim3(threads), 0, s, rec, p.T, p.tok_tile, p.E, p.r,
+                       p.kk, p.k, p.n_act, (uint32_t)p.n_sub, partial, pcnt);
+  else
+    hipLaunchKernelGGL((score_kernel<CAP, false>), grid, dim3(threads), 0, s, rec, p.T, p.tok_tile, p.E, p.r,
+                       p.kk, p.k, p.n_act, (uint32_t)p.n_sub, partial, pcnt);
 }
 
 int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
