@@ -22,5 +22,7 @@ from .moe_reference import (  # noqa: F401
     skip_decision,
     forward_skip,
     median_skip_ratio,
+    skip_topk_decision,
+    forward_skip_topk,
 )
 from .brute_force import brute_force_enumerate  # noqa: F401

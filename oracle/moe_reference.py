@@ -247,13 +247,85 @@ def forward_skip(x, Wgate, W1, W3, W2, beta: float, logits=None, kept=None):
     return out, skip, e0, e1
 
 
-def median_skip_ratio(logits) -> float:
+def median_skip_ratio(logits, kept=None) -> float:
     """beta of Sec. 3.3 / App. A.7: the median over tokens of w_e1 / w_e0.
 
-    For an even token count the mean of the two middle order statistics.
+    For an even token count the mean of the two middle order statistics.  With
+    `kept`, e0 and e1 are the top-2 among the kept experts (the pruned layer).
     """
     l64 = np.asarray(logits, dtype=np.float64)
+    if kept is not None:
+        allowed = np.zeros(l64.shape[1], dtype=bool)
+        allowed[list(kept)] = True
+        l64 = np.where(allowed[None, :], l64, -np.inf)
     order = routing_order(l64)
     t = np.arange(l64.shape[0])
     rho = np.exp(l64[t, order[:, 1]] - l64[t, order[:, 0]])
     return float(np.median(rho))
+
+
+def skip_topk_decision(logits: np.ndarray, k: int, beta: float, kept=None):
+    """Generalised dynamic skipping for top-k routing (appendix on the theory of skipping).
+
+    Per token, with w_1 >= ... >= w_k the weights of its top-k experts (among `kept`
+    if given; ties to the lower index), keep the top-i* experts where
+        i* = min { i in 1..k : sum_{m>i} w_m <= beta * sum_{m<=k} w_m }.
+    Any common factor of the weights cancels, so w_m = exp(l_m - l_1) is used.  The
+    paper fixes no precision for this decision; it is taken in fp64 on the fp32
+    logits, the tail sums accumulated from the smallest weight upwards, and the GPU
+    kernel does the same.
+
+    Returns experts [T,k] (descending weight), i_star [T], w [T,k] fp64 (un-normalised).
+    """
+    l32 = np.asarray(logits, dtype=np.float32)
+    T, E = l32.shape
+    l64 = l32.astype(np.float64)
+    if kept is not None:
+        allowed = np.zeros(E, dtype=bool)
+        allowed[list(kept)] = True
+        if allowed.sum() < k:
+            raise ValueError("top-k routing needs at least k kept experts")
+        l64 = np.where(allowed[None, :], l64, -np.inf)
+    experts = routing_order(l64)[:, :k]
+    b = float(np.float32(beta))
+    i_star = np.zeros(T, dtype=np.int64)
+    w = np.zeros((T, k), dtype=np.float64)
+    for t in range(T):
+        lt = l64[t, experts[t]]
+        wt = np.exp(lt - lt[0])
+        tail = np.zeros(k + 1)                       # tail[i] = sum_{m>i} w_m, 1-based m
+        for i in range(k - 1, -1, -1):
+            tail[i] = tail[i + 1] + wt[i]
+        total = tail[0]
+        i = 1
+        while tail[i] > b * total:                   # tail[k] = 0 always passes
+            i += 1
+        i_star[t] = i
+        w[t] = wt
+    return experts, i_star, w
+
+
+def forward_skip_topk(x, Wgate, W1, W3, W2, k: int, beta: float, logits=None, kept=None):
+    """MoE forward with the generalised skipping rule: each token's output is Eq. 2 over
+    its top-i* experts, weights renormalised over those i* (the reduced output of the
+    theory appendix).  Only routed (token, expert) pairs go through an expert.
+
+    Returns out [T,H], i_star [T], experts [T,k].
+    """
+    x = np.asarray(x, dtype=np.float64)
+    if logits is None:
+        logits = x @ np.asarray(Wgate, dtype=np.float64).T
+    experts, i_star, _ = skip_topk_decision(logits, k, beta, kept)
+    out = np.zeros_like(x)
+    T = x.shape[0]
+    lsel = np.take_along_axis(np.asarray(logits, dtype=np.float64), experts, axis=1)
+    w = np.exp(lsel - lsel[:, :1])                 # the decision is in fp32 logits, the weights are not
+    used = np.arange(k)[None, :] < i_star[:, None]                 # [T,k]
+    coef = np.where(used, w, 0.0)
+    coef = coef / coef.sum(axis=1, keepdims=True)
+    for e in range(len(W1)):
+        for m in range(k):
+            rows = np.nonzero((experts[:, m] == e) & used[:, m])[0]
+            if len(rows):
+                out[rows] += coef[rows, m][:, None] * expert_ffn(x[rows], W1[e], W3[e], W2[e])
+    return out, i_star, experts

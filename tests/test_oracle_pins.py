@@ -376,3 +376,84 @@ def test_pruned_skip_forward_reduces_to_known_cases():
     assert np.all(e0 == 3) and np.all(e1 == 4)
     with pytest.raises(ValueError):
         oracle.skip_decision(forced, 0.5, kept=(2,))
+
+
+# ---- generalised top-k skipping (theory appendix) -------------------------------------------
+
+def test_topk_skip_reduces_to_known_cases():
+    x, Wg, W1, W3, W2 = skip_case(21, T=60, E=6)
+    logits, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    # beta = 0: nothing is skipped, the output is Eq. 2 with k experts
+    for k in (1, 2, 3, 4):
+        out, i_star, experts = oracle.forward_skip_topk(x, Wg, W1, W3, W2, k, 0.0)
+        assert np.all(i_star == k)
+        np.testing.assert_allclose(out, oracle.layer_output(logits, Y, k), rtol=1e-11, atol=1e-13)
+        assert np.array_equal(experts, oracle.routing_order(logits)[:, :k])
+    # beta >= 1: sum_{m>1} w_m <= sum_m w_m always, so only the best expert stays
+    out, i_star, experts = oracle.forward_skip_topk(x, Wg, W1, W3, W2, 4, 1.0)
+    assert np.all(i_star == 1)
+    t = np.arange(60)
+    np.testing.assert_allclose(out, Y[experts[:, 0], t], rtol=1e-11, atol=1e-13)
+    # k = 2: w_2 <= b (w_1 + w_2)  <=>  w_2 <= b / (1 - b) w_1, the rule of Sec. 3.3 with
+    # beta = b / (1 - b) (the appendix's "abuse of notation"); compare with the top-2 code path
+    b = 0.3
+    out_g, i_star, _ = oracle.forward_skip_topk(x, Wg, W1, W3, W2, 2, b)
+    out_2, skip, _, _ = oracle.forward_skip(x, Wg, W1, W3, W2, b / (1 - b))
+    assert 0 < skip.sum() < 60
+    assert np.array_equal(i_star == 1, skip)
+    np.testing.assert_allclose(out_g, out_2, rtol=1e-11, atol=1e-13)
+
+
+def test_topk_skip_rule_by_hand_and_monotone():
+    # weights proportional to 8 : 4 : 2 : 1 (logits ln 8, ln 4, ln 2, 0): tails 7/15, 3/15, 1/15, 0
+    logits = np.log(np.array([[4.0, 1.0, 8.0, 2.0, 1e-3]], dtype=np.float64)).astype(np.float32)
+    want = {0.0: 4, 0.05: 4, 0.07: 3, 0.19: 3, 0.21: 2, 0.45: 2, 0.47: 1, 1.0: 1}
+    for beta, i_want in want.items():
+        experts, i_star, w = oracle.skip_topk_decision(logits, 4, beta)
+        assert list(experts[0]) == [2, 0, 3, 1]
+        assert i_star[0] == i_want, beta
+    g = rng(22)
+    lg = g.standard_normal((500, 8)).astype(np.float32)
+    prev = None
+    for beta in (0.0, 0.02, 0.1, 0.2, 0.4, 0.8, 1.0):
+        _, i_star, _ = oracle.skip_topk_decision(lg, 4, beta)
+        assert np.all((1 <= i_star) & (i_star <= 4))
+        if prev is not None:
+            assert np.all(i_star <= prev)            # a larger budget never keeps more experts
+        prev = i_star
+    # kept set: experts outside it never appear
+    experts, _, _ = oracle.skip_topk_decision(lg, 3, 0.1, kept=(0, 2, 5, 7))
+    assert set(np.unique(experts)) <= {0, 2, 5, 7}
+
+
+def test_topk_skip_error_bound():
+    # Theory appendix: ||z_hat - z|| <= (sum_{m>i} w_m / sum_{m<=k} w_m) D whenever D bounds every
+    # pairwise distance ||f_m - f_n|| of the token's top-k expert outputs; and the chosen i*
+    # therefore keeps the error below beta * D.
+    x, Wg, W1, W3, W2 = skip_case(23, T=80, E=8)
+    logits, Y = oracle.expert_outputs(x, Wg, W1, W3, W2)
+    k, beta = 4, 0.15
+    out_s, i_star, experts = oracle.forward_skip_topk(x, Wg, W1, W3, W2, k, beta)
+    full = oracle.layer_output(logits, Y, k)
+    assert len(np.unique(i_star)) > 1
+    for t in range(80):
+        f = Y[experts[t], t]                                   # [k, H]
+        D = max(np.linalg.norm(f[m] - f[n]) for m in range(k) for n in range(m))
+        w = np.exp(logits[t, experts[t]])
+        frac = w[i_star[t]:].sum() / w.sum()
+        err = np.linalg.norm(out_s[t] - full[t])
+        assert err <= frac * D * (1 + 1e-9) + 1e-12     # rounding of two summation orders when nothing is skipped
+        assert frac <= beta + 1e-12
+        if i_star[t] > 1:                                      # i* is minimal
+            assert w[i_star[t] - 1:].sum() / w.sum() > beta
+
+
+def test_median_skip_ratio_with_kept_set():
+    g = rng(24)
+    lg = g.standard_normal((301, 8)).astype(np.float32)
+    kept = (1, 2, 4, 7)
+    beta = oracle.median_skip_ratio(lg, kept=kept)
+    sub = np.sort(lg[:, list(kept)].astype(np.float64), axis=1)
+    rho = np.sort(np.exp(sub[:, -2] - sub[:, -1]))
+    assert beta == pytest.approx(rho[150], rel=1e-15)          # odd count: the middle one
+    assert oracle.median_skip_ratio(lg, kept=range(8)) == oracle.median_skip_ratio(lg)
