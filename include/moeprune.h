@@ -124,6 +124,37 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
                             float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
                             void* hip_stream);
 
+/* ---- moe_forward_skip_topk -------------------------------------------------- */
+/* Dynamic skipping for top-k routing, 1 <= k <= 8 (appendix on the theory of dynamic skipping).
+ * Per token, with w_1 >= ... >= w_k the Eq. 1 weights of its top-k experts among `kept_mask`
+ * (ties to the lower index), the top-i* experts stay, where
+ *     i* = min { i in 1..k : sum_{m>i} w_m <= beta * sum_{m<=k} w_m },
+ * and out = sum_{m<=i*} w_m E_m(x) / sum_{m<=i*} w_m.  beta = 0 keeps all k (Eq. 2), beta >= 1
+ * keeps only the best expert.  For k = 2 this is the rule of moe_forward_skip with its beta set
+ * to b / (1 - b) (up to "<" against "<=").  The decision is taken in fp64 on the fp32 logits.
+ *   x, weights, out, logits_out as in moe_forward_skip
+ *   n_used [T] int32 (out): i* per token
+ *   topk_out [T,k] int32 (out, may be NULL): the top-k experts, best first
+ * Workspace: moe_forward_skip_topk_workspace (grows with k). */
+size_t moe_forward_skip_topk_workspace(int64_t T, int E, int H, int F, moep_dtype dt, int k);
+int moe_forward_skip_topk(const void* x, const void* Wgate, const void* W1, const void* W3,
+                          const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                          uint32_t kept_mask, float beta, void* out, int32_t* n_used,
+                          float* logits_out, int32_t* topk_out, void* ws, size_t ws_bytes,
+                          void* hip_stream);
+
+/* ---- skip_calibrate_beta ---------------------------------------------------- */
+/* The threshold of Sec. 3.3 as the paper sets it (Sec. 3.3; appendix on experiment details):
+ * the median over the T calibration tokens of w_e1 / w_e0 = exp(l_e1 - l_e0), e0 and e1 the
+ * token's top-2 experts among `kept_mask`.  For even T the mean of the two middle values.  The
+ * order statistics are selected exactly on the fp32 differences l_e1 - l_e0.
+ *   logits [T,E] fp32, T >= 1;  beta_out [1] fp32 (DEVICE, out)
+ * Passing the result to moe_forward_skip on the same tokens skips half of them (within 1/T
+ * when no two tokens share the same difference). */
+size_t skip_calibrate_beta_workspace(int64_t T);
+int skip_calibrate_beta(const float* logits, int64_t T, int E, uint32_t kept_mask, float* beta_out,
+                        void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- per-kernel timing (for benchmarks) ------------------------------------ */
 /* While enabled, every kernel launch is bracketed by HIP events on its stream.
  * moep_timing_collect waits for the recorded events, adds them up per kernel and

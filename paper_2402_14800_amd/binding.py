@@ -25,6 +25,8 @@ EXPORTS = (
     "moe_expert_outputs_workspace", "moe_expert_outputs",
     "prune_enumerate_workspace", "prune_enumerate",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
+    "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
+    "skip_calibrate_beta_workspace", "skip_calibrate_beta",
     "moep_timing_enable", "moep_timing_collect",
 )
 
@@ -73,6 +75,16 @@ def _load() -> ctypes.CDLL:
     lib.moe_forward_pruned_skip.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_uint32,
                                                              c_float, c_void_p, c_void_p, c_void_p, c_void_p,
                                                              c_void_p, c_size_t, c_void_p]
+    lib.moe_forward_skip_topk_workspace.restype = c_size_t
+    lib.moe_forward_skip_topk_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, c_int]
+    lib.moe_forward_skip_topk.restype = c_int
+    lib.moe_forward_skip_topk.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_uint32,
+                                                           c_float, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                           c_void_p, c_size_t, c_void_p]
+    lib.skip_calibrate_beta_workspace.restype = c_size_t
+    lib.skip_calibrate_beta_workspace.argtypes = [c_int64]
+    lib.skip_calibrate_beta.restype = c_int
+    lib.skip_calibrate_beta.argtypes = [c_void_p, c_int64, c_int, c_uint32, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.moep_timing_enable.restype = c_int
     lib.moep_timing_enable.argtypes = [c_int]
     lib.moep_timing_collect.restype = c_int
@@ -218,6 +230,43 @@ def moe_forward_skip(x, Wgate, W1, W3, W2, beta: float, k: int = 2, workspace=No
 
 def moe_forward_pruned_skip(x, Wgate, W1, W3, W2, kept_mask: int, beta: float, **kw):
     return moe_forward_skip(x, Wgate, W1, W3, W2, beta, kept_mask=kept_mask, **kw)
+
+
+def moe_forward_skip_topk(x, Wgate, W1, W3, W2, k: int, beta: float, kept_mask: Optional[int] = None,
+                          workspace=None, want_logits: bool = True, want_topk: bool = True):
+    """out [T,H], n_used [T] int32 (i* per token), logits [T,E] fp32 (or None), topk [T,k] int32 (or None)."""
+    dev = _dev(x, Wgate, W1, W3, W2)
+    dt = _dtype_code(x)
+    T, H = x.shape
+    E, F, _ = W1.shape
+    assert Wgate.shape == (E, H) and W3.shape == (E, F, H) and W2.shape == (E, H, F)
+    if kept_mask is None:
+        kept_mask = (1 << E) - 1
+    out = torch.empty((T, H), dtype=x.dtype, device=dev)
+    n_used = torch.empty((T,), dtype=torch.int32, device=dev)
+    logits = torch.empty((T, E), dtype=torch.float32, device=dev) if want_logits else None
+    topk = torch.empty((T, max(k, 1)), dtype=torch.int32, device=dev) if want_topk else None
+    need = _lib.moe_forward_skip_topk_workspace(T, E, H, F, dt, k)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.moe_forward_skip_topk(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt, k,
+                                      c_uint32(kept_mask), c_float(beta), _ptr(out), _ptr(n_used),
+                                      _ptr(logits), _ptr(topk), _ptr(ws), ws.numel(), _stream(dev)))
+    return out, n_used, logits, topk
+
+
+def skip_calibrate_beta(logits, kept_mask: Optional[int] = None, workspace=None) -> torch.Tensor:
+    """beta [1] fp32 on the device: the median of w_e1 / w_e0 over the rows of logits [T,E]."""
+    dev = _dev(logits)
+    assert logits.dtype == torch.float32 and logits.dim() == 2
+    T, E = logits.shape
+    if kept_mask is None:
+        kept_mask = (1 << E) - 1
+    beta = torch.empty((1,), dtype=torch.float32, device=dev)
+    need = _lib.skip_calibrate_beta_workspace(T)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.skip_calibrate_beta(_ptr(logits), T, E, c_uint32(kept_mask), _ptr(beta), _ptr(ws), ws.numel(),
+                                    _stream(dev)))
+    return beta
 
 
 # ---------------------------------------------------------------- kernel timing

@@ -253,10 +253,39 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
 }
 
 // ------------------------------------------------------------------ moe_forward_skip
+// The two grouped GEMMs of the routed path: every slot (one routed (token, expert) pair, rows grouped
+// by expert) goes through its expert, and the down projection scales it by the slot's routing weight.
+static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, const void* W3,
+                          const void* W2, moep_dtype dt, char* w, hipStream_t s) {
+  const int H = p.H, F = p.F;
+  GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
+  up.A = x; up.lda = H; up.a_rows = (const int32_t*)(w + p.off_slot_token);
+  up.B0 = W1; up.B1 = W3; up.b_expert_stride = (int64_t)F * H;
+  up.C = w + p.off_h; up.ldc = F;
+  up.M = p.max_slots; up.N = F; up.K = H;
+  up.epilogue = EPI_SWIGLU;
+  up.tile_expert = (const int32_t*)(w + p.off_tile_expert);
+  up.tile_row0 = (const int32_t*)(w + p.off_tile_row0);
+  up.seg_end = (const int32_t*)(w + p.off_seg_end);
+  up.max_m_tiles = p.max_tiles;
+  if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu_routed")) return st;
+
+  GemmArgs down;                    // slot_out[slot] = weight(slot) * h[slot] W2[e]^T, fp32
+  down.A = w + p.off_h; down.lda = F;
+  down.B0 = W2; down.b_expert_stride = (int64_t)H * F;
+  down.C = w + p.off_slot_out; down.ldc = H;
+  down.M = p.max_slots; down.N = H; down.K = F;
+  down.epilogue = EPI_ROWSCALE_F32;
+  down.row_scale = (const float*)(w + p.off_slot_scale);
+  down.tile_expert = up.tile_expert; down.tile_row0 = up.tile_row0; down.seg_end = up.seg_end;
+  down.max_m_tiles = p.max_tiles;
+  return run_gemm(down, dt, s, "gemm_down_routed");
+}
+
 size_t moe_forward_skip_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {
   if (!valid_shape(T, E, H, F, dt, "moe_forward_skip_workspace")) return 0;
   SkipPlan p;
-  if (plan_skip(T, E, H, F, dt, &p)) return 0;
+  if (plan_skip(T, E, H, F, dt, 2, &p)) return 0;
   return p.total;
 }
 
@@ -286,7 +315,7 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
   if (T == 0) return MOEP_OK;
   if (!x || !out || !skip_mask) return fail(MOEP_EINVAL, "%s: NULL x, out or skip_mask", who);
   SkipPlan p;
-  if (int st = plan_skip(T, E, H, F, dt, &p)) return st;
+  if (int st = plan_skip(T, E, H, F, dt, 2, &p)) return st;
   if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   char* w = (char*)ws;
@@ -296,30 +325,65 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   if (int st = launch_skip_routing(p, logits, kept_mask, beta, skip_mask, top2_out, w, s)) return st;
 
-  GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
-  up.A = x; up.lda = H; up.a_rows = (const int32_t*)(w + p.off_slot_token);
-  up.B0 = W1; up.B1 = W3; up.b_expert_stride = (int64_t)F * H;
-  up.C = w + p.off_h; up.ldc = F;
-  up.M = p.max_slots; up.N = F; up.K = H;
-  up.epilogue = EPI_SWIGLU;
-  up.tile_expert = (const int32_t*)(w + p.off_tile_expert);
-  up.tile_row0 = (const int32_t*)(w + p.off_tile_row0);
-  up.seg_end = (const int32_t*)(w + p.off_seg_end);
-  up.max_m_tiles = p.max_tiles;
-  if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu_routed")) return st;
-
-  GemmArgs down;                    // slot_out[slot] = weight(slot) * h[slot] W2[e]^T, fp32
-  down.A = w + p.off_h; down.lda = F;
-  down.B0 = W2; down.b_expert_stride = (int64_t)H * F;
-  down.C = w + p.off_slot_out; down.ldc = H;
-  down.M = p.max_slots; down.N = H; down.K = F;
-  down.epilogue = EPI_ROWSCALE_F32;
-  down.row_scale = (const float*)(w + p.off_slot_scale);
-  down.tile_expert = up.tile_expert; down.tile_row0 = up.tile_row0; down.seg_end = up.seg_end;
-  down.max_m_tiles = p.max_tiles;
-  if (int st = run_gemm(down, dt, s, "gemm_down_routed")) return st;
+  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s)) return st;
   (void)es;
   return launch_skip_combine(p, dt, skip_mask, out, w, s);
+}
+
+
+// ------------------------------------------------------------------ moe_forward_skip_topk
+size_t moe_forward_skip_topk_workspace(int64_t T, int E, int H, int F, moep_dtype dt, int k) {
+  if (!valid_shape(T, E, H, F, dt, "moe_forward_skip_topk_workspace")) return 0;
+  if (k < 1 || k > 8) return 0;
+  SkipPlan p;
+  if (plan_skip(T, E, H, F, dt, k, &p)) return 0;
+  return p.total;
+}
+
+int moe_forward_skip_topk(const void* x, const void* Wgate, const void* W1, const void* W3,
+                          const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                          uint32_t kept_mask, float beta, void* out, int32_t* n_used,
+                          float* logits_out, int32_t* topk_out, void* ws, size_t ws_bytes,
+                          void* hip_stream) {
+  const char* who = "moe_forward_skip_topk";
+  if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
+  if (k < 1) return fail(MOEP_EINVAL, "%s: k=%d must be at least 1", who, k);
+  if (k > 8) return fail(MOEP_EUNSUPPORTED, "%s: k=%d (at most 8 experts per token)", who, k);
+  if (E < 32 && (kept_mask >> E)) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x has bits beyond expert %d", who, kept_mask, E - 1);
+  if (__builtin_popcount(kept_mask) < k) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x keeps fewer than k=%d experts", who, kept_mask, k);
+  if (!(beta >= 0.0f) || std::isinf(beta)) return fail(MOEP_EINVAL, "%s: beta must be finite and >= 0", who);
+  if (int st = check_alignment(H, F, dt, who)) return st;
+  if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (T == 0) return MOEP_OK;
+  if (!x || !out || !n_used) return fail(MOEP_EINVAL, "%s: NULL x, out or n_used", who);
+  SkipPlan p;
+  if (int st = plan_skip(T, E, H, F, dt, k, &p)) return st;
+  if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* w = (char*)ws;
+  float* logits = logits_out ? logits_out : (float*)(w + p.off_logits);
+  if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
+  if (int st = launch_skip_topk_routing(p, logits, kept_mask, beta, n_used, topk_out, w, s)) return st;
+  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s)) return st;
+  return launch_skip_topk_combine(p, dt, out, w, s);
+}
+
+// ------------------------------------------------------------------ skip_calibrate_beta
+size_t skip_calibrate_beta_workspace(int64_t T) {
+  if (T < 1 || T >= ((int64_t)1 << 32)) return 0;
+  return calibrate_workspace_bytes(T);
+}
+
+int skip_calibrate_beta(const float* logits, int64_t T, int E, uint32_t kept_mask, float* beta_out,
+                        void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "skip_calibrate_beta";
+  if (T < 1 || T >= ((int64_t)1 << 32)) return fail(MOEP_EINVAL, "%s: T=%lld (the median needs at least one token)", who, (long long)T);
+  if (E < 2 || E > 32) return fail(MOEP_EINVAL, "%s: E=%d out of range 2..32", who, E);
+  if (E < 32 && (kept_mask >> E)) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x has bits beyond expert %d", who, kept_mask, E - 1);
+  if (__builtin_popcount(kept_mask) < 2) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x keeps fewer than two experts", who, kept_mask);
+  if (!logits || !beta_out) return fail(MOEP_EINVAL, "%s: NULL logits or beta_out", who);
+  if (int st = check_ws(ws, ws_bytes, calibrate_workspace_bytes(T), who)) return st;
+  return launch_calibrate_beta(logits, T, E, kept_mask, beta_out, (char*)ws, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

@@ -92,16 +92,25 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
 // ---- skipping ---------------------------------------------------------------------
 struct SkipPlan {
   int64_t T; int E, H, F;
-  int64_t max_slots;     // 2 T
+  int ks;                // slots per token (2 for the top-2 rule, k for the generalised rule)
+  int64_t max_slots;     // ks T
   int64_t max_tiles;     // upper bound on M tiles over all experts
   size_t off_logits, off_slot_token, off_slot_scale, off_pos, off_counts, off_seg_end,
          off_tile_expert, off_tile_row0, off_h, off_slot_out, total;
 };
-int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, SkipPlan* p);
+int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p);
 int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,
                         int32_t* top2_out, char* ws, hipStream_t s);
 int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
                         char* ws, hipStream_t s);
+int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta,
+                             int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s);
+int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s);
+
+// ---- beta calibration -----------------------------------------------------------------
+size_t calibrate_workspace_bytes(int64_t T);
+int launch_calibrate_beta(const float* logits, int64_t T, int E, uint32_t kept_mask, float* beta_out,
+                          char* ws, hipStream_t s);
 
 // Host-side subset helpers (also used to fill the device mask table).
 int64_t binomial(int n, int r);

@@ -11,6 +11,11 @@
 //            expert's segment the rows are in ascending token order, so the result is reproducible.
 //   combine  out[t] = slot_out[pos0] (+ slot_out[pos1] unless skipped); the down projection has
 //            already multiplied each slot by its weight.  No atomics anywhere on this path.
+//
+// The *_topk kernels are the same pipeline for the generalised rule of the theory appendix: each
+// token keeps the top-i* of its top-k experts, i* = min { i : sum_{m>i} w_m <= beta sum_{m<=k} w_m },
+// decided in fp64 on the fp32 logits (tail sums accumulated from the smallest weight upwards), and
+// the kept weights are renormalised over those i*.
 #include <cmath>
 
 #include "common.h"
@@ -167,20 +172,148 @@ __global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__
   }
 }
 
+
+// ---- generalised top-k skipping -----------------------------------------------------------
+template <int K>
+__global__ __launch_bounds__(RB) void route_topk_kernel(const float* __restrict__ logits, int64_t T,
+                                                        int E, uint32_t kept, double beta,
+                                                        int32_t* __restrict__ n_used,
+                                                        int32_t* __restrict__ topk,
+                                                        float* __restrict__ tw,
+                                                        int32_t* __restrict__ counts) {
+  __shared__ int cnt[32];
+  if (threadIdx.x < 32) cnt[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t t = (int64_t)blockIdx.x * RB + threadIdx.x;
+  if (t < T) {
+    const float* l = logits + t * E;
+    uint32_t avail = kept;
+    int es[K];
+    double ex[K];
+    float l_first = 0.f;
+#pragma unroll
+    for (int m = 0; m < K; ++m) {            // m-th largest kept logit; strict >: lower index wins a tie
+      int best = -1;
+      float bv = 0.f;
+      for (int e = 0; e < E; ++e) {
+        if (!((avail >> e) & 1u)) continue;
+        const float v = l[e];
+        if (best < 0 || v > bv) { best = e; bv = v; }
+      }
+      avail &= ~(1u << best);
+      es[m] = best;
+      if (m == 0) l_first = bv;
+      ex[m] = exp((double)bv - (double)l_first);
+    }
+    double tail[K + 1];                      // tail[i] = sum_{m > i} w_m (m counted from 1)
+    tail[K] = 0.0;
+#pragma unroll
+    for (int i = K - 1; i >= 0; --i) tail[i] = tail[i + 1] + ex[i];
+    const double budget = beta * tail[0];
+    int istar = K;
+#pragma unroll
+    for (int i = K - 1; i >= 1; --i)
+      if (!(tail[i] > budget)) istar = i;    // ends at the smallest i that passes; tail[K] = 0 always passes
+    // tails shrink with i, so "passes" is monotone and the smallest passing i is the answer
+    double den = 0.0;
+#pragma unroll
+    for (int m = 0; m < K; ++m)
+      if (m < istar) den += ex[m];
+    n_used[t] = istar;
+#pragma unroll
+    for (int m = 0; m < K; ++m) {
+      topk[t * K + m] = es[m];
+      tw[t * K + m] = m < istar ? (float)(ex[m] / den) : 0.0f;
+      if (m < istar) atomicAdd(&cnt[es[m]], 1);
+    }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < E) counts[(int64_t)blockIdx.x * E + threadIdx.x] = cnt[threadIdx.x];
+}
+
+template <int K>
+__global__ __launch_bounds__(RB) void scatter_topk_kernel(const int32_t* __restrict__ topk,
+                                                          const float* __restrict__ tw,
+                                                          const int32_t* __restrict__ n_used,
+                                                          const int32_t* __restrict__ base, int64_t T,
+                                                          int E, int32_t* __restrict__ slot_token,
+                                                          float* __restrict__ slot_scale,
+                                                          int32_t* __restrict__ pos) {
+  __shared__ int wave_cnt[RB / 64][32];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * RB + threadIdx.x;
+  const bool live = t < T;
+  const int nu = live ? n_used[t] : 0;
+  int es[K], rank[K];
+#pragma unroll
+  for (int m = 0; m < K; ++m) { es[m] = m < nu ? topk[t * K + m] : -1; rank[m] = 0; }
+  const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int e = 0; e < E; ++e) {             // a token routes to an expert at most once
+    bool has = false;
+#pragma unroll
+    for (int m = 0; m < K; ++m) has |= es[m] == e;
+    const unsigned long long b = __ballot(has);
+    const int before = __popcll(b & below);
+#pragma unroll
+    for (int m = 0; m < K; ++m)
+      if (es[m] == e) rank[m] = before;
+    if (lane == 0) wave_cnt[wave][e] = __popcll(b);
+  }
+  __syncthreads();
+  if (!live) return;
+#pragma unroll
+  for (int m = 0; m < K; ++m) {
+    int p = -1;
+    if (es[m] >= 0) {
+      p = base[(int64_t)blockIdx.x * E + es[m]] + rank[m];
+      for (int w = 0; w < wave; ++w) p += wave_cnt[w][es[m]];
+      slot_token[p] = (int32_t)t;
+      slot_scale[p] = tw[t * K + m];
+    }
+    pos[t * K + m] = p;
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_topk_kernel(const float4* __restrict__ slot_out,
+                                                           const int32_t* __restrict__ pos, int64_t T,
+                                                           int H4, int K, void* __restrict__ out) {
+  const int64_t n = T * H4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t t = i / H4;
+    const int c = (int)(i - t * H4);
+    float4 v = slot_out[(int64_t)pos[t * K] * H4 + c];     // the best expert is always kept
+    for (int m = 1; m < K; ++m) {
+      const int p = pos[t * K + m];
+      if (p < 0) break;                                   // kept experts are a prefix of the top-k
+      const float4 u = slot_out[(int64_t)p * H4 + c];
+      v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    if (BF16) {
+      uint2 o;
+      o.x = bf16_rne(v.x) | (bf16_rne(v.y) << 16);
+      o.y = bf16_rne(v.z) | (bf16_rne(v.w) << 16);
+      ((uint2*)out)[i] = o;
+    } else {
+      ((float4*)out)[i] = v;
+    }
+  }
+}
+
 }  // namespace
 
-int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, SkipPlan* p) {
-  if (2 * T >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "moe_forward_skip: T too large");
-  p->T = T; p->E = E; p->H = H; p->F = F;
-  p->max_slots = 2 * T;
-  p->max_tiles = ceil_div(2 * T, GEMM_BM) + E;
+int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p) {
+  if ((int64_t)ks * T >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "moe_forward_skip: T too large");
+  p->T = T; p->E = E; p->H = H; p->F = F; p->ks = ks;
+  p->max_slots = (int64_t)ks * T;
+  p->max_tiles = ceil_div((int64_t)ks * T, GEMM_BM) + E;
   const int64_t n_blocks = ceil_div(T, RB);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
   p->off_logits = take((size_t)T * E * 4);
   p->off_slot_token = take((size_t)p->max_slots * 4);
   p->off_slot_scale = take((size_t)p->max_slots * 4);
-  p->off_pos = take((size_t)T * 2 * 4 * 3);            // pos, top2, weights: [T,2] each
+  p->off_pos = take((size_t)T * ks * 4 * 3);           // pos, experts, weights: [T,ks] each
   p->off_counts = take((size_t)n_blocks * E * 4);
   p->off_seg_end = take((size_t)E * 4);
   p->off_tile_expert = take((size_t)p->max_tiles * 4);
@@ -226,6 +359,62 @@ int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_ma
   else
     hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(256), 0, s,
                        (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+
+int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta,
+                             int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s) {
+  const int64_t T = p.T;
+  const int K = p.ks;
+  int32_t* pos = (int32_t*)(ws + p.off_pos);
+  int32_t* topk = topk_out ? topk_out : pos + (int64_t)K * T;
+  float* tw = (float*)(pos + 2 * (int64_t)K * T);
+  int32_t* counts = (int32_t*)(ws + p.off_counts);
+  const int64_t n_blocks = ceil_div(T, RB);
+  int32_t* slot_token = (int32_t*)(ws + p.off_slot_token);
+  float* slot_scale = (float*)(ws + p.off_slot_scale);
+  Timed t("skip_route_dispatch", s);
+#define MOEP_ROUTE_CASE(KK)                                                                    \
+  case KK:                                                                                    \
+    hipLaunchKernelGGL(route_topk_kernel<KK>, dim3((unsigned)n_blocks), dim3(RB), 0, s, logits, T, p.E, \
+                       kept_mask, (double)beta, n_used, topk, tw, counts);                    \
+    break;
+  switch (K) {
+    MOEP_ROUTE_CASE(1) MOEP_ROUTE_CASE(2) MOEP_ROUTE_CASE(3) MOEP_ROUTE_CASE(4)
+    MOEP_ROUTE_CASE(5) MOEP_ROUTE_CASE(6) MOEP_ROUTE_CASE(7) MOEP_ROUTE_CASE(8)
+    default: return fail(MOEP_EUNSUPPORTED, "moe_forward_skip_topk: k=%d (1..8)", K);
+  }
+#undef MOEP_ROUTE_CASE
+  hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, counts, n_blocks, p.E,
+                     (int32_t*)(ws + p.off_seg_end), (int32_t*)(ws + p.off_tile_expert),
+                     (int32_t*)(ws + p.off_tile_row0), (int)p.max_tiles);
+#define MOEP_SCATTER_CASE(KK)                                                                  \
+  case KK:                                                                                    \
+    hipLaunchKernelGGL(scatter_topk_kernel<KK>, dim3((unsigned)n_blocks), dim3(RB), 0, s, topk, tw, \
+                       n_used, counts, T, p.E, slot_token, slot_scale, pos);                  \
+    break;
+  switch (K) {
+    MOEP_SCATTER_CASE(1) MOEP_SCATTER_CASE(2) MOEP_SCATTER_CASE(3) MOEP_SCATTER_CASE(4)
+    MOEP_SCATTER_CASE(5) MOEP_SCATTER_CASE(6) MOEP_SCATTER_CASE(7) MOEP_SCATTER_CASE(8)
+  }
+#undef MOEP_SCATTER_CASE
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s) {
+  const int H4 = p.H / 4;
+  const int64_t n = p.T * H4;
+  const unsigned blocks = (unsigned)(ceil_div(n, 256) < 65536 ? ceil_div(n, 256) : 65536);
+  Timed t("skip_combine", s);
+  if (dt == MOEP_BF16)
+    hipLaunchKernelGGL(combine_topk_kernel<true>, dim3(blocks), dim3(256), 0, s,
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, p.ks, out);
+  else
+    hipLaunchKernelGGL(combine_topk_kernel<false>, dim3(blocks), dim3(256), 0, s,
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, p.ks, out);
   MOEP_HIP(hipGetLastError());
   return MOEP_OK;
 }

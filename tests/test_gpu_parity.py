@@ -402,3 +402,94 @@ def test_pruned_skip_forward_matches_oracle_and_enumeration(dtype, E, H, F, T, r
     torch.cuda.synchronize()
     assert torch.equal(same.view(torch.int16 if dtype == "bf16" else torch.int32),
                        ref2.view(torch.int16 if dtype == "bf16" else torch.int32)) and torch.equal(sk1, sk2)
+
+
+# ------------------------------------------------------------------ generalised top-k skipping, beta calibration
+TOPK_CASES = [
+    # dtype, E, H, F, T, k, beta, kept
+    ("bf16", 8, 256, 512, 900, 4, 0.15, None),
+    ("bf16", 16, 128, 256, 700, 4, 0.05, None),        # the E=16, k=4 shape of the stress configuration
+    ("f32", 6, 64, 128, 300, 3, 0.2, (0, 2, 3, 5)),
+    ("bf16", 8, 128, 256, 500, 2, 0.3, None),          # k = 2: equals the top-2 rule with beta / (1 - beta)
+    ("bf16", 8, 128, 256, 400, 8, 0.1, None),          # every expert selected
+    ("bf16", 8, 128, 256, 300, 1, 0.5, None),          # top-1: nothing to skip
+    ("bf16", 8, 128, 256, 300, 4, 0.0, None),          # never skip: Eq. 2 with k = 4
+    ("bf16", 8, 128, 256, 300, 4, 1.0, (1, 2, 4, 6, 7)),   # always down to the best kept expert
+]
+
+
+@pytest.mark.parametrize("dtype,E,H,F,T,k,beta,kept", TOPK_CASES)
+def test_moe_forward_skip_topk_matches_oracle(dtype, E, H, F, T, k, beta, kept):
+    cfg, layer = small_layer(dtype, E, min(k, 2), H, F, T, index=12)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    mask = None if kept is None else sum(1 << e for e in kept)
+    beta = float(np.float32(beta))
+    out_t, n_used_t, logits_t, topk_t = pkg.moe_forward_skip_topk(*ws, k, beta, kept_mask=mask)
+    torch.cuda.synchronize()
+    logits_full, _ = pkg.moe_expert_outputs(*ws)
+    torch.cuda.synchronize()
+    assert torch.equal(logits_t, logits_full)
+    args = [wl.to_f64(layer[n]) for n in ("x", "Wgate", "W1", "W3", "W2")]
+    ref_out, i_star, experts = oracle.forward_skip_topk(*args, k, beta, logits=logits_t.cpu().numpy(), kept=kept)
+    assert np.array_equal(topk_t.cpu().numpy(), experts)
+    assert np.array_equal(n_used_t.cpu().numpy(), i_star)
+    check_outputs(wl.to_f64(out_t), ref_out, "top-k skip out")
+    if beta == 0.0:
+        assert np.all(i_star == k)
+    elif beta >= 1.0:
+        assert np.all(i_star == 1)
+    elif k > 2:
+        assert len(np.unique(i_star)) > 1               # the case exercises more than one branch
+    if k == 2 and kept is None:
+        # same tokens skipped, same output bits as the top-2 entry point with the converted threshold
+        # (a token sitting exactly on the threshold would differ: "<" there, "<=" here)
+        out2, skip2, _, top2 = pkg.moe_forward_skip(*ws, float(np.float32(beta / (1 - beta))))
+        torch.cuda.synchronize()
+        assert torch.equal(top2, topk_t)
+        agree = (skip2.cpu().numpy().astype(bool) == (i_star == 1))
+        assert agree.mean() >= 1 - 2.0 / T
+        check_outputs(wl.to_f64(out2)[agree], ref_out[agree], "top-2 entry point vs generalised rule")
+
+
+def test_skip_topk_empty_batch_and_reuse_of_workspace():
+    cfg, layer = small_layer("bf16", 8, 2, 128, 256, 64, index=12)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    out, n_used, _, _ = pkg.moe_forward_skip_topk(d["x"][:0].contiguous(), *ws[1:], 4, 0.1)
+    torch.cuda.synchronize()
+    assert out.shape == (0, 128) and n_used.numel() == 0
+    a = pkg.moe_forward_skip_topk(*ws, 4, 0.1)
+    b = pkg.moe_forward_skip_topk(*ws, 4, 0.1)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)) and torch.equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("T,E,kept", [(1, 4, None), (2, 4, None), (1000, 8, None), (1001, 8, None),
+                                      (70000, 8, None), (4097, 16, (0, 3, 5, 6, 9, 12)), (5000, 32, None)])
+def test_skip_calibrate_beta_matches_oracle(T, E, kept):
+    g = np.random.default_rng(1234 + T + E)
+    logits = (g.standard_normal((T, E)) * 1.3).astype(np.float32)
+    if T >= 1000:
+        logits[5] = logits[7]                           # duplicated token: equal keys
+        logits[9, :] = 0.25                              # all logits equal: ratio exactly 1
+    mask = None if kept is None else sum(1 << e for e in kept)
+    beta_t = pkg.skip_calibrate_beta(torch.from_numpy(logits).to(DEV), kept_mask=mask)
+    torch.cuda.synchronize()
+    beta = float(beta_t.item())
+    ref = oracle.median_skip_ratio(logits, kept=kept)
+    assert beta == pytest.approx(ref, rel=2e-6)          # fp32 differences, fp32 result
+    if T >= 1000:
+        _, _, skip, _ = oracle.skip_decision(logits, beta, kept=kept)
+        assert abs(skip.mean() - 0.5) <= 2.0 / T
+
+
+def test_calibrated_beta_feeds_the_skip_forward():
+    cfg, layer = small_layer("bf16", 8, 2, 128, 256, 1024, index=13)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    logits_t, _ = pkg.moe_expert_outputs(*ws)
+    beta = float(pkg.skip_calibrate_beta(logits_t).item())
+    _, skip_t, _, _ = pkg.moe_forward_skip(*ws, beta)
+    torch.cuda.synchronize()
+    assert abs(float(skip_t.float().mean().item()) - 0.5) <= 2.0 / 1024

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "moeprune.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moep?_\w+|prune_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(moep?_\w+|prune_\w+|skip_\w+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -107,6 +107,26 @@ def test_argument_errors_come_back_as_status_codes():
     assert fp(*pargs(0b1)) == 1                   # fewer than two kept experts
     assert fp(*pargs(0b1_0000_0011)) == 1         # bit beyond E = 8
     assert fp(*pargs(0b11, k=3)) == 2
+    ft = binding._lib.moe_forward_skip_topk
+    assert ft(*pargs(0xff, k=0)) == 1
+    assert ft(*pargs(0xff, k=9)) == 2
+    assert ft(*pargs(0b111, k=4)) == 1            # fewer kept experts than k
+    assert ft(*pargs(0xff, k=4, beta=-1.0)) == 1
+    assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 4) > \
+        binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 2) > 0
+    assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 2) == \
+        binding._lib.moe_forward_skip_workspace(1024, 8, 64, 128, 1)
+    assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 9) == 0
+    cal = binding._lib.skip_calibrate_beta
+    cargs = lambda **kw: [one, kw.get("T", 64), kw.get("E", 8), ctypes.c_uint32(kw.get("mask", 0xff)), one, one,
+                          kw.get("ws", 1 << 40), None]
+    assert cal(*cargs(T=0)) == 1
+    assert cal(*cargs(E=1)) == 1
+    assert cal(*cargs(mask=0b100)) == 1
+    assert cal(*cargs(mask=0x1ff)) == 1
+    assert cal(*cargs(ws=64)) == 3
+    assert binding._lib.skip_calibrate_beta_workspace(0) == 0
+    assert binding._lib.skip_calibrate_beta_workspace(1000) >= 4000
     g = binding._lib.moe_expert_outputs
     gargs = lambda **kw: [one] * 5 + [kw.get("T", 64), kw.get("E", 8), kw.get("H", 64), kw.get("F", 128),
                                       kw.get("dt", 1), one, one, one, kw.get("ws", 1 << 40), None]
