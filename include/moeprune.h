@@ -155,6 +155,18 @@ size_t skip_calibrate_beta_workspace(int64_t T);
 int skip_calibrate_beta(const float* logits, int64_t T, int E, uint32_t kept_mask, float* beta_out,
                         void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- expert_selection_stats -------------------------------------------------- */
+/* Selection statistics of a calibration set, and the activation-frequency baseline built on them
+ * (Sec. 4.1, comparison with other expert pruning baselines; appendix on expert selection tendency).
+ *   logits [T,E] fp32; top-k by logit, ties to the lower index, 1 <= k <= E
+ *   count [E] int64 (out): tokens whose top-k contains expert e
+ *   coselect [E,E] int64 (out): tokens whose top-k contains both i and j (diagonal = count)
+ *   frequency_mask [1] uint32 (out, may be NULL): kept mask of the baseline that discards the
+ *     E - r least selected experts (on equal counts the lower index is kept); r is ignored if NULL
+ * Outputs are overwritten, not accumulated.  T = 0 gives zeros. */
+int expert_selection_stats(const float* logits, int64_t T, int E, int k, int r, int64_t* count,
+                           int64_t* coselect, uint32_t* frequency_mask, void* hip_stream);
+
 /* ---- per-kernel timing (for benchmarks) ------------------------------------ */
 /* While enabled, every kernel launch is bracketed by HIP events on its stream.
  * moep_timing_collect waits for the recorded events, adds them up per kernel and

@@ -24,5 +24,7 @@ from .moe_reference import (  # noqa: F401
     median_skip_ratio,
     skip_topk_decision,
     forward_skip_topk,
+    expert_selection_stats,
+    frequency_kept,
 )
 from .brute_force import brute_force_enumerate  # noqa: F401

@@ -329,3 +329,32 @@ def forward_skip_topk(x, Wgate, W1, W3, W2, k: int, beta: float, logits=None, ke
             if len(rows):
                 out[rows] += coef[rows, m][:, None] * expert_ffn(x[rows], W1[e], W3[e], W2[e])
     return out, i_star, experts
+
+
+def expert_selection_stats(logits: np.ndarray, k: int):
+    """Selection statistics over a calibration set (baselines of Sec. 4.1; appendix on expert
+    selection tendency): count[e] = number of tokens whose top-k contains expert e, and
+    co[i, j] = number of tokens whose top-k contains both i and j (so co[e, e] = count[e]).
+    Top-k as everywhere else: larger logit first, ties to the lower index.
+    """
+    order = routing_order(np.asarray(logits))
+    T, E = order.shape
+    count = np.zeros(E, dtype=np.int64)
+    co = np.zeros((E, E), dtype=np.int64)
+    for t in range(T):
+        chosen = order[t, :k]
+        for i in chosen:
+            count[i] += 1
+            for j in chosen:
+                co[i, j] += 1
+    return count, co
+
+
+def frequency_kept(count: np.ndarray, r: int):
+    """The activation-frequency baseline of Sec. 4.1: discard the experts selected least often,
+    i.e. keep the r most frequently selected.  The paper does not say what happens on equal
+    counts; the lower index is kept.  Returns the kept experts as a sorted tuple.
+    """
+    E = len(count)
+    ranked = sorted(range(E), key=lambda e: (-int(count[e]), e))
+    return tuple(sorted(ranked[:r]))

@@ -26,7 +26,7 @@ EXPORTS = (
     "prune_enumerate_workspace", "prune_enumerate",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
-    "skip_calibrate_beta_workspace", "skip_calibrate_beta",
+    "skip_calibrate_beta_workspace", "skip_calibrate_beta", "expert_selection_stats",
     "moep_timing_enable", "moep_timing_collect",
 )
 
@@ -85,6 +85,9 @@ def _load() -> ctypes.CDLL:
     lib.skip_calibrate_beta_workspace.argtypes = [c_int64]
     lib.skip_calibrate_beta.restype = c_int
     lib.skip_calibrate_beta.argtypes = [c_void_p, c_int64, c_int, c_uint32, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.expert_selection_stats.restype = c_int
+    lib.expert_selection_stats.argtypes = [c_void_p, c_int64, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                           c_void_p]
     lib.moep_timing_enable.restype = c_int
     lib.moep_timing_enable.argtypes = [c_int]
     lib.moep_timing_collect.restype = c_int
@@ -267,6 +270,19 @@ def skip_calibrate_beta(logits, kept_mask: Optional[int] = None, workspace=None)
     _check(_lib.skip_calibrate_beta(_ptr(logits), T, E, c_uint32(kept_mask), _ptr(beta), _ptr(ws), ws.numel(),
                                     _stream(dev)))
     return beta
+
+
+def expert_selection_stats(logits, k: int, r: Optional[int] = None):
+    """count [E] int64, coselect [E,E] int64, frequency_mask (int32 view of the uint32 mask, [1]) or None."""
+    dev = _dev(logits)
+    assert logits.dtype == torch.float32 and logits.dim() == 2
+    T, E = logits.shape
+    count = torch.empty((E,), dtype=torch.int64, device=dev)
+    co = torch.empty((E, E), dtype=torch.int64, device=dev)
+    fmask = torch.empty((1,), dtype=torch.int32, device=dev) if r is not None else None
+    _check(_lib.expert_selection_stats(_ptr(logits), T, E, k, r if r is not None else 0, _ptr(count), _ptr(co),
+                                       _ptr(fmask), _stream(dev)))
+    return count, co, fmask
 
 
 # ---------------------------------------------------------------- kernel timing

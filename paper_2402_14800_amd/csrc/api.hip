@@ -386,4 +386,18 @@ int skip_calibrate_beta(const float* logits, int64_t T, int E, uint32_t kept_mas
   return launch_calibrate_beta(logits, T, E, kept_mask, beta_out, (char*)ws, (hipStream_t)hip_stream);
 }
 
+
+// ------------------------------------------------------------------ expert_selection_stats
+int expert_selection_stats(const float* logits, int64_t T, int E, int k, int r, int64_t* count,
+                           int64_t* coselect, uint32_t* frequency_mask, void* hip_stream) {
+  const char* who = "expert_selection_stats";
+  if (T < 0) return fail(MOEP_EINVAL, "%s: T=%lld is negative", who, (long long)T);
+  if (E < 1 || E > 32) return fail(MOEP_EINVAL, "%s: E=%d out of range 1..32", who, E);
+  if (k < 1 || k > E) return fail(MOEP_EINVAL, "%s: k=%d out of range 1..E", who, k);
+  if (!count || !coselect) return fail(MOEP_EINVAL, "%s: NULL count or coselect", who);
+  if (T > 0 && !logits) return fail(MOEP_EINVAL, "%s: NULL logits", who);
+  if (frequency_mask && (r < 1 || r > E)) return fail(MOEP_EINVAL, "%s: r=%d out of range 1..E", who, r);
+  return launch_selection_stats(logits, T, E, k, r, count, coselect, frequency_mask, (hipStream_t)hip_stream);
+}
+
 }  // extern "C"

@@ -112,6 +112,10 @@ size_t calibrate_workspace_bytes(int64_t T);
 int launch_calibrate_beta(const float* logits, int64_t T, int E, uint32_t kept_mask, float* beta_out,
                           char* ws, hipStream_t s);
 
+// ---- selection statistics ---------------------------------------------------------------
+int launch_selection_stats(const float* logits, int64_t T, int E, int k, int r, int64_t* count, int64_t* co,
+                           uint32_t* freq_mask, hipStream_t s);
+
 // Host-side subset helpers (also used to fill the device mask table).
 int64_t binomial(int n, int r);
 uint32_t unrank_mask(int E, int r, int64_t idx);

@@ -493,3 +493,39 @@ def test_calibrated_beta_feeds_the_skip_forward():
     _, skip_t, _, _ = pkg.moe_forward_skip(*ws, beta)
     torch.cuda.synchronize()
     assert abs(float(skip_t.float().mean().item()) - 0.5) <= 2.0 / 1024
+
+
+# ------------------------------------------------------------------ selection statistics, frequency baseline
+@pytest.mark.parametrize("T,E,k,r", [(1000, 8, 2, 6), (70001, 8, 2, 4), (3000, 16, 4, 8), (500, 32, 8, 20),
+                                     (300, 5, 5, 2), (257, 4, 1, 3), (0, 8, 2, 6)])
+def test_expert_selection_stats_match_oracle(T, E, k, r):
+    g = np.random.default_rng(77 + T + E)
+    logits = (g.standard_normal((T, E)) + 0.3 * g.standard_normal((1, E))).astype(np.float32)
+    if T >= 300:
+        logits[3, :] = 1.0                               # all equal: the k lowest indices are selected
+        logits[4, 1] = logits[4, 0]                      # a tie at the top
+    count_t, co_t, fmask_t = pkg.expert_selection_stats(torch.from_numpy(logits).to(DEV), k, r)
+    torch.cuda.synchronize()
+    count, co = oracle.expert_selection_stats(logits, k)
+    assert np.array_equal(count_t.cpu().numpy(), count)
+    assert np.array_equal(co_t.cpu().numpy(), co)
+    kept = oracle.frequency_kept(count, r)
+    assert (int(fmask_t.item()) & 0xFFFFFFFF) == sum(1 << e for e in kept)
+
+
+def test_frequency_baseline_is_scored_by_the_enumeration():
+    # the baseline's kept set is one of the enumerated subsets: its Eq. 3 loss can be read off the
+    # loss vector, and can be no smaller than the minimum the enumeration found
+    E, r = 8, 6
+    cfg, layer = small_layer("bf16", E, 2, 128, 256, 800, index=14)
+    d = to_dev(layer)
+    logits_t, Y_t = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    loss, amin, amask, _ = run_enumerate(logits_t, Y_t, 2, r)
+    _, _, fmask_t = pkg.expert_selection_stats(logits_t, 2, r)
+    fmask = int(fmask_t.item()) & 0xFFFFFFFF
+    idx = pkg.subset_rank(E, r, fmask)
+    assert 0 <= idx < len(loss) and loss[idx] >= loss[amin]
+    kept = [e for e in range(E) if (fmask >> e) & 1]
+    l64 = logits_t.cpu().numpy().astype(np.float64)
+    ref = oracle.pruned_layer_output(l64, wl.to_f64(Y_t), kept, 2) - oracle.layer_output(l64, wl.to_f64(Y_t), 2)
+    assert loss[idx] == pytest.approx(float((ref ** 2).sum()), rel=LOSS_RTOL)

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "moeprune.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moep?_\w+|prune_\w+|skip_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(moep?_\w+|prune_\w+|skip_\w+|expert_\w+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -127,6 +127,14 @@ def test_argument_errors_come_back_as_status_codes():
     assert cal(*cargs(ws=64)) == 3
     assert binding._lib.skip_calibrate_beta_workspace(0) == 0
     assert binding._lib.skip_calibrate_beta_workspace(1000) >= 4000
+    st = binding._lib.expert_selection_stats
+    sargs = lambda **kw: [one, kw.get("T", 64), kw.get("E", 8), kw.get("k", 2), kw.get("r", 4),
+                          kw.get("count", one), one, kw.get("fm", one), None]
+    assert st(*sargs(E=33)) == 1
+    assert st(*sargs(k=0)) == 1 and st(*sargs(k=9)) == 1
+    assert st(*sargs(r=0)) == 1 and st(*sargs(r=9)) == 1
+    assert st(*sargs(count=None)) == 1
+    assert st(*sargs(T=-1)) == 1
     g = binding._lib.moe_expert_outputs
     gargs = lambda **kw: [one] * 5 + [kw.get("T", 64), kw.get("E", 8), kw.get("H", 64), kw.get("F", 128),
                                       kw.get("dt", 1), one, one, one, kw.get("ws", 1 << 40), None]

@@ -457,3 +457,47 @@ def test_median_skip_ratio_with_kept_set():
     rho = np.sort(np.exp(sub[:, -2] - sub[:, -1]))
     assert beta == pytest.approx(rho[150], rel=1e-15)          # odd count: the middle one
     assert oracle.median_skip_ratio(lg, kept=range(8)) == oracle.median_skip_ratio(lg)
+
+
+# ---- selection statistics and the frequency baseline ------------------------------------------
+
+def test_selection_stats_hand_example_and_invariants():
+    # three tokens, four experts, k = 2: selections {2,0}, {2,3}, {1,0} (second token ties 3 with 1? no: 3 wins by value)
+    logits = np.array([[2.0, 0.0, 3.0, 1.0],
+                       [0.0, 1.0, 5.0, 4.0],
+                       [3.0, 7.0, 0.0, 3.0]], dtype=np.float32)    # last row: experts 0 and 3 tie, lower index wins
+    count, co = oracle.expert_selection_stats(logits, 2)
+    assert count.tolist() == [2, 1, 2, 1]
+    want = np.zeros((4, 4), dtype=np.int64)
+    for pair in ((2, 0), (2, 3), (1, 0)):
+        for i in pair:
+            for j in pair:
+                want[i, j] += 1
+    assert np.array_equal(co, want)
+    g = rng(31)
+    lg = g.standard_normal((400, 8)).astype(np.float32)
+    for k in (1, 2, 4, 8):
+        count, co = oracle.expert_selection_stats(lg, k)
+        assert count.sum() == 400 * k
+        assert np.array_equal(np.diag(co), count)
+        assert np.array_equal(co, co.T)
+        assert np.array_equal(co.sum(axis=1), k * count)
+        if k == 1:
+            assert np.array_equal(count, np.bincount(np.argmax(lg, axis=1), minlength=8))
+        if k == 8:
+            assert np.all(co == 400)
+    # k = 2 co-selection against the top-2 pairs the skipping code path reports
+    e0, e1, _, _ = oracle.skip_decision(lg, 0.0)
+    _, co = oracle.expert_selection_stats(lg, 2)
+    pairs = np.zeros((8, 8), dtype=np.int64)
+    np.add.at(pairs, (e0, e1), 1)
+    off = co - np.diag(np.diag(co))
+    assert np.array_equal(off, pairs + pairs.T)
+
+
+def test_frequency_baseline_keeps_most_selected():
+    assert oracle.frequency_kept(np.array([5, 9, 1, 7]), 2) == (1, 3)
+    assert oracle.frequency_kept(np.array([5, 9, 1, 7]), 3) == (0, 1, 3)
+    assert oracle.frequency_kept(np.array([4, 4, 4, 4]), 2) == (0, 1)          # ties: lower index kept
+    assert oracle.frequency_kept(np.array([3, 8, 3, 8, 3]), 3) == (0, 1, 3)
+    assert oracle.frequency_kept(np.array([1, 2, 3]), 3) == (0, 1, 2)
