@@ -93,6 +93,32 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
                     int k, int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
                     int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- rank-limited expert pass ---------------------------------------------- */
+/* A layer pruned to r experts routes a token to the first min(k,r) KEPT experts of its ranking
+ * (Sec. 3.2); at most E - r experts are missing, so only the token's first
+ * n_act = min(E, min(k,r) + E - r) ranked experts can ever be selected by any of the C(E,r)
+ * pruned layers (or by the full layer).  moe_expert_outputs_ranked therefore runs each token
+ * through its n_rank best-ranked experts only -- n_rank / E of the FLOPs of moe_expert_outputs --
+ * and prune_enumerate_ranked scores the subsets from those outputs; the losses are the same real
+ * numbers as prune_enumerate's whenever n_rank >= n_act.
+ *   n_rank: 1 .. min(E, 8)
+ *   logits [T,E] fp32 (out)
+ *   ranked_experts [T,n_rank] int32 (out): the token's experts by descending logit, ties to the lower index
+ *   slot_of [T,n_rank] int32 (out): row of Yr holding the output of ranked_experts[t,j] on token t
+ *   Yr [T*n_rank, H] dt (out): expert outputs, rows grouped by expert, ascending token within an expert;
+ *     row slot_of[t,j] is bit-identical to Y[ranked_experts[t,j], t, :] of moe_expert_outputs
+ * prune_enumerate_ranked: arguments as prune_enumerate, with (ranked_experts, slot_of, Yr, n_rank)
+ * in place of Y; n_rank < n_act(k, r) is MOEP_EINVAL.  Workspace: prune_enumerate_workspace. */
+size_t moe_expert_outputs_ranked_workspace(int64_t T, int E, int H, int F, moep_dtype dt, int n_rank);
+int moe_expert_outputs_ranked(const void* x, const void* Wgate, const void* W1, const void* W3,
+                              const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
+                              int n_rank, float* logits, int32_t* ranked_experts, int32_t* slot_of,
+                              void* Yr, void* ws, size_t ws_bytes, void* hip_stream);
+int prune_enumerate_ranked(const float* logits, const int32_t* ranked_experts, const int32_t* slot_of,
+                           const void* Yr, int64_t T, int E, int H, moep_dtype dt, int n_rank, int k,
+                           int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                           int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- moe_forward_skip ------------------------------------------------------ */
 /* Sec. 3.3 with the output of App. A.2, k = 2: per token take the top-2 experts
  * e0, e1; skip e1 iff w_e1 < beta * w_e0, decided as (l_e1 - l_e0) < ln(beta) in

@@ -27,6 +27,7 @@ EXPORTS = (
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
     "skip_calibrate_beta_workspace", "skip_calibrate_beta", "expert_selection_stats",
+    "moe_expert_outputs_ranked_workspace", "moe_expert_outputs_ranked", "prune_enumerate_ranked",
     "moep_timing_enable", "moep_timing_collect",
 )
 
@@ -88,6 +89,16 @@ def _load() -> ctypes.CDLL:
     lib.expert_selection_stats.restype = c_int
     lib.expert_selection_stats.argtypes = [c_void_p, c_int64, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
                                            c_void_p]
+    lib.moe_expert_outputs_ranked_workspace.restype = c_size_t
+    lib.moe_expert_outputs_ranked_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, c_int]
+    lib.moe_expert_outputs_ranked.restype = c_int
+    lib.moe_expert_outputs_ranked.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int,
+                                                               c_void_p, c_void_p, c_void_p, c_void_p,
+                                                               c_void_p, c_size_t, c_void_p]
+    lib.prune_enumerate_ranked.restype = c_int
+    lib.prune_enumerate_ranked.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int, c_int, c_int,
+                                           c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_size_t, c_void_p]
     lib.moep_timing_enable.restype = c_int
     lib.moep_timing_enable.argtypes = [c_int]
     lib.moep_timing_collect.restype = c_int
@@ -199,6 +210,52 @@ def prune_enumerate(logits, Y, k: int, r: int, workspace=None, count_unaffected:
     _check(_lib.prune_enumerate(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
                                 _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
     return loss, argmin, amask, unaffected
+
+
+def moe_expert_outputs_ranked(x, Wgate, W1, W3, W2, n_rank: int, workspace=None, out=None):
+    """logits [T,E] fp32, ranked_experts [T,n_rank] int32, slot_of [T,n_rank] int32, Yr [T*n_rank,H].
+    `out` may carry a previous call's (logits, ranked_experts, slot_of, Yr) to be overwritten."""
+    dev = _dev(x, Wgate, W1, W3, W2)
+    dt = _dtype_code(x)
+    T, H = x.shape
+    E, F, _ = W1.shape
+    assert Wgate.shape == (E, H) and W3.shape == (E, F, H) and W2.shape == (E, H, F)
+    if out is None:
+        logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+        experts = torch.empty((T, max(n_rank, 1)), dtype=torch.int32, device=dev)
+        slot_of = torch.empty((T, max(n_rank, 1)), dtype=torch.int32, device=dev)
+        Yr = torch.empty((T * max(n_rank, 1), H), dtype=x.dtype, device=dev)
+    else:
+        logits, experts, slot_of, Yr = out
+    need = _lib.moe_expert_outputs_ranked_workspace(T, E, H, F, dt, n_rank)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.moe_expert_outputs_ranked(_ptr(x), _ptr(Wgate), _ptr(W1), _ptr(W3), _ptr(W2), T, E, H, F, dt,
+                                          n_rank, _ptr(logits), _ptr(experts), _ptr(slot_of), _ptr(Yr),
+                                          _ptr(ws), ws.numel(), _stream(dev)))
+    return logits, experts, slot_of, Yr
+
+
+def prune_enumerate_ranked(logits, experts, slot_of, Yr, k: int, r: int, workspace=None,
+                           count_unaffected: bool = True):
+    """As prune_enumerate, from the outputs of moe_expert_outputs_ranked."""
+    dev = _dev(logits, Yr)
+    dt = _dtype_code(Yr)
+    T, E = logits.shape
+    n_rank = experts.shape[1]
+    H = Yr.shape[1]
+    n_sub = num_subsets(E, r)
+    if n_sub < 0:
+        raise MoepError(1, f"r={r} out of range for E={E}")
+    loss = torch.empty((n_sub,), dtype=torch.float32, device=dev)
+    argmin = torch.empty((1,), dtype=torch.int32, device=dev)
+    amask = torch.empty((1,), dtype=torch.int32, device=dev)
+    unaff = torch.empty((1,), dtype=torch.int64, device=dev) if count_unaffected else None
+    need = _lib.prune_enumerate_workspace(T, E, H, k, r, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.prune_enumerate_ranked(_ptr(logits), _ptr(experts), _ptr(slot_of), _ptr(Yr), T, E, H, dt, n_rank,
+                                       k, r, _ptr(loss), _ptr(argmin), _ptr(amask), _ptr(unaff), _ptr(ws),
+                                       ws.numel(), _stream(dev)))
+    return loss, argmin, amask, unaff
 
 
 def moe_forward_skip_workspace(T: int, E: int, H: int, F: int, dtype_code: int) -> int:

@@ -255,8 +255,10 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
 // ------------------------------------------------------------------ moe_forward_skip
 // The two grouped GEMMs of the routed path: every slot (one routed (token, expert) pair, rows grouped
 // by expert) goes through its expert, and the down projection scales it by the slot's routing weight.
+// With `plain_out` the down projection instead stores the unscaled expert output of every slot there,
+// in the storage dtype.
 static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, const void* W3,
-                          const void* W2, moep_dtype dt, char* w, hipStream_t s) {
+                          const void* W2, moep_dtype dt, char* w, hipStream_t s, void* plain_out = nullptr) {
   const int H = p.H, F = p.F;
   GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
   up.A = x; up.lda = H; up.a_rows = (const int32_t*)(w + p.off_slot_token);
@@ -273,10 +275,10 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
   GemmArgs down;                    // slot_out[slot] = weight(slot) * h[slot] W2[e]^T, fp32
   down.A = w + p.off_h; down.lda = F;
   down.B0 = W2; down.b_expert_stride = (int64_t)H * F;
-  down.C = w + p.off_slot_out; down.ldc = H;
+  down.C = plain_out ? plain_out : w + p.off_slot_out; down.ldc = H;
   down.M = p.max_slots; down.N = H; down.K = F;
-  down.epilogue = EPI_ROWSCALE_F32;
-  down.row_scale = (const float*)(w + p.off_slot_scale);
+  down.epilogue = plain_out ? EPI_STORE : EPI_ROWSCALE_F32;
+  down.row_scale = plain_out ? nullptr : (const float*)(w + p.off_slot_scale);
   down.tile_expert = up.tile_expert; down.tile_row0 = up.tile_row0; down.seg_end = up.seg_end;
   down.max_m_tiles = p.max_tiles;
   return run_gemm(down, dt, s, "gemm_down_routed");
@@ -398,6 +400,65 @@ int expert_selection_stats(const float* logits, int64_t T, int E, int k, int r, 
   if (T > 0 && !logits) return fail(MOEP_EINVAL, "%s: NULL logits", who);
   if (frequency_mask && (r < 1 || r > E)) return fail(MOEP_EINVAL, "%s: r=%d out of range 1..E", who, r);
   return launch_selection_stats(logits, T, E, k, r, count, coselect, frequency_mask, (hipStream_t)hip_stream);
+}
+
+
+// ------------------------------------------------------------------ rank-limited expert pass
+size_t moe_expert_outputs_ranked_workspace(int64_t T, int E, int H, int F, moep_dtype dt, int n_rank) {
+  if (!valid_shape(T, E, H, F, dt, "moe_expert_outputs_ranked_workspace")) return 0;
+  if (n_rank < 1 || n_rank > 8 || n_rank > E) return 0;
+  SkipPlan p;
+  if (plan_skip(T, E, H, F, dt, n_rank, &p, false)) return 0;
+  return p.total;
+}
+
+int moe_expert_outputs_ranked(const void* x, const void* Wgate, const void* W1, const void* W3,
+                              const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
+                              int n_rank, float* logits, int32_t* ranked_experts, int32_t* slot_of,
+                              void* Yr, void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "moe_expert_outputs_ranked";
+  if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
+  if (n_rank < 1 || n_rank > E) return fail(MOEP_EINVAL, "%s: n_rank=%d out of range 1..E", who, n_rank);
+  if (n_rank > 8) return fail(MOEP_EUNSUPPORTED, "%s: n_rank=%d (at most 8)", who, n_rank);
+  if (int st = check_alignment(H, F, dt, who)) return st;
+  if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (T == 0) return MOEP_OK;
+  if (!x || !logits || !ranked_experts || !slot_of || !Yr)
+    return fail(MOEP_EINVAL, "%s: NULL x, logits, ranked_experts, slot_of or Yr", who);
+  SkipPlan p;
+  if (int st = plan_skip(T, E, H, F, dt, n_rank, &p, false)) return st;
+  if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* w = (char*)ws;
+  if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
+  const uint32_t all = E < 32 ? (1u << E) - 1u : 0xffffffffu;
+  // beta = 0 keeps all n_rank experts of every token; the [T, n_rank] region of the workspace that would
+  // hold the expert ids (they go to ranked_experts instead) takes the per-token counts.
+  int32_t* n_used = (int32_t*)(w + p.off_pos) + (int64_t)n_rank * T;
+  if (int st = launch_skip_topk_routing(p, logits, all, 0.0f, n_used, ranked_experts, w, s, slot_of)) return st;
+  return run_routed_ffn(p, x, W1, W3, W2, dt, w, s, Yr);
+}
+
+int prune_enumerate_ranked(const float* logits, const int32_t* ranked_experts, const int32_t* slot_of,
+                           const void* Yr, int64_t T, int E, int H, moep_dtype dt, int n_rank, int k,
+                           int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                           int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "prune_enumerate_ranked";
+  if (!valid_shape(T, E, H, 1, dt, who)) return MOEP_EINVAL;
+  EnumPlan p;
+  if (int st = plan_enumerate(T, E, H, k, r, &p)) return st;
+  if (n_rank < p.n_act || n_rank > E || n_rank > 16)
+    return fail(MOEP_EINVAL, "%s: n_rank=%d, but k=%d, r=%d can select any of a token's first %d ranked experts",
+                who, n_rank, k, r, p.n_act);
+  if (H % (dt == MOEP_BF16 ? 64 : 1))
+    return fail(MOEP_EUNSUPPORTED, "%s: H=%d must be a multiple of 64 for bf16", who, H);
+  if (!loss || !argmin || !argmin_mask) return fail(MOEP_EINVAL, "%s: NULL loss, argmin or argmin_mask", who);
+  if (T > 0 && (!logits || !ranked_experts || !slot_of || !Yr))
+    return fail(MOEP_EINVAL, "%s: NULL logits, ranked_experts, slot_of or Yr", who);
+  if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
+  RankedSource src{slot_of, ranked_experts, n_rank};
+  return launch_enumerate(p, logits, Yr, dt, loss, argmin, argmin_mask, unaffected_pairs, (char*)ws,
+                          (hipStream_t)hip_stream, &src);
 }
 
 }  // extern "C"

@@ -85,9 +85,16 @@ struct EnumPlan {
   size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, total;
 };
 int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p);
+// Expert outputs of the rank-limited pass: row slot_of[t, j] of Y is the output of expert
+// experts[t, j], the token's j-th ranked expert, j < n_rank.
+struct RankedSource {
+  const int32_t* slot_of;
+  const int32_t* experts;
+  int n_rank;
+};
 int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
                      float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
-                     char* ws, hipStream_t s);
+                     char* ws, hipStream_t s, const RankedSource* ranked = nullptr);
 
 // ---- skipping ---------------------------------------------------------------------
 struct SkipPlan {
@@ -98,13 +105,14 @@ struct SkipPlan {
   size_t off_logits, off_slot_token, off_slot_scale, off_pos, off_counts, off_seg_end,
          off_tile_expert, off_tile_row0, off_h, off_slot_out, total;
 };
-int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p);
+int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p, bool with_slot_out = true);
 int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,
                         int32_t* top2_out, char* ws, hipStream_t s);
 int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
                         char* ws, hipStream_t s);
 int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta,
-                             int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s);
+                             int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s,
+                             int32_t* pos_out = nullptr);
 int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s);
 
 // ---- beta calibration -----------------------------------------------------------------

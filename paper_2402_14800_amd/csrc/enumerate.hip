@@ -156,6 +156,87 @@ __global__ __launch_bounds__(256) void gram_f32_kernel(const float* __restrict__
     }
 }
 
+
+// ------------------------------------------------------------------ Gram from ranked expert outputs
+// The rank-limited expert pass stores, per token, only the outputs of its n best-ranked experts, as
+// rows of Yr addressed through slot_of[t, j]; experts[t, j] names the expert.  G keeps its expert
+// indexing: entry (e_i, e_j) of token t is written for the token's n ranked experts only, which is
+// every entry the routing-prep kernel reads as long as n >= n_act.
+template <int EPAD>
+__global__ __launch_bounds__(256) void gram_ranked_bf16_kernel(const uint4* __restrict__ Yr,
+                                                               const int32_t* __restrict__ slot_of,
+                                                               const int32_t* __restrict__ experts,
+                                                               float* __restrict__ G, int64_t T, int E,
+                                                               int n, int H) {
+  constexpr int TPT = 16 / EPAD;
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t t0 = tile * TPT;
+  if (t0 >= T) return;
+  const int row = lane & 15, kg = lane >> 4;
+  const int j = row % EPAD;
+  const int64_t t = t0 + row / EPAD;
+  const bool valid = j < n && t < T;
+  const int chunks = H / 8;
+  const uint4* src = Yr + (int64_t)(valid ? slot_of[t * n + j] : 0) * chunks + kg;
+
+  f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+  const int steps = H / 32;
+  for (int s0 = 0; s0 < steps; s0 += 8) {
+    uint4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int s = s0 + i;
+      v[i] = (valid && s < steps) ? src[s * 4] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+      const bf16x8 a0 = __builtin_bit_cast(bf16x8, v[i]);
+      const bf16x8 a1 = __builtin_bit_cast(bf16x8, v[i + 1]);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, a0, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, a1, acc1, 0, 0, 0);
+    }
+  }
+  const int col = lane & 15;
+  const int cj = col % EPAD;
+  const int64_t ct = t0 + col / EPAD;
+  if (ct >= T || cj >= n) return;
+  const int ce = experts[ct * n + cj];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int r = 4 * (lane >> 4) + v;
+    const int rj = r % EPAD;
+    if (r / EPAD == col / EPAD && rj < n) {
+      const int re = experts[ct * n + rj];
+      G[(ct * E + re) * E + ce] = acc0[v] + acc1[v];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void gram_ranked_f32_kernel(const float* __restrict__ Yr,
+                                                              const int32_t* __restrict__ slot_of,
+                                                              const int32_t* __restrict__ experts,
+                                                              float* __restrict__ G, int64_t T, int E,
+                                                              int n, int H) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  for (int i = 0; i < n; ++i)
+    for (int j = i; j < n; ++j) {
+      const float* yi = Yr + (int64_t)slot_of[t * n + i] * H;
+      const float* yj = Yr + (int64_t)slot_of[t * n + j] * H;
+      float s = 0.f;
+      for (int h = lane; h < H; h += 64) s = fmaf(yi[h], yj[h], s);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+      if (lane == 0) {
+        const int ei = experts[t * n + i], ej = experts[t * n + j];
+        G[(t * E + ei) * E + ej] = s;
+        G[(t * E + ej) * E + ei] = s;
+      }
+    }
+}
+
 // ------------------------------------------------------------------ record layout
 // Per token, CAP = capacity >= n_act, all fp32 unless noted:
 //   [0, CAP)            ex_j  = exp(l_j - l_0), l in rank order (0 beyond n_act)
@@ -435,7 +516,7 @@ static void launch_score(const EnumPlan& p, const float* rec, float* partial, ui
 
 int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
                      float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
-                     char* ws, hipStream_t s) {
+                     char* ws, hipStream_t s, const RankedSource* ranked) {
   float* G = (float*)(ws + p.off_gram);
   float* rec = (float*)(ws + p.off_rec);
   float* partial = (float*)(ws + p.off_partial);
@@ -445,7 +526,21 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
     {
       Timed t("gram", s);
       const unsigned per_tok_blocks = (unsigned)ceil_div(p.T, 4);
-      if (dt == MOEP_BF16) {
+      if (ranked) {
+        const int n = ranked->n_rank;
+        if (dt != MOEP_BF16)
+          hipLaunchKernelGGL(gram_ranked_f32_kernel, dim3(per_tok_blocks), dim3(256), 0, s, (const float*)Y,
+                             ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+        else if (n <= 4)
+          hipLaunchKernelGGL(gram_ranked_bf16_kernel<4>, dim3((unsigned)ceil_div(p.T, 16)), dim3(256), 0, s,
+                             (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+        else if (n <= 8)
+          hipLaunchKernelGGL(gram_ranked_bf16_kernel<8>, dim3((unsigned)ceil_div(p.T, 8)), dim3(256), 0, s,
+                             (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+        else
+          hipLaunchKernelGGL(gram_ranked_bf16_kernel<16>, dim3(per_tok_blocks), dim3(256), 0, s,
+                             (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+      } else if (dt == MOEP_BF16) {
         if (p.E <= 4)
           hipLaunchKernelGGL(gram_bf16_16_kernel<4>, dim3((unsigned)ceil_div(p.T, 16)), dim3(256), 0, s, (const uint4*)Y, G, p.T, p.E, p.H);
         else if (p.E <= 8)

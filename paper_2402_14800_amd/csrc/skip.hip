@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void combine_topk_kernel(const float4* __restr
 
 }  // namespace
 
-int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p) {
+int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p, bool with_slot_out) {
   if ((int64_t)ks * T >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "moe_forward_skip: T too large");
   p->T = T; p->E = E; p->H = H; p->F = F; p->ks = ks;
   p->max_slots = (int64_t)ks * T;
@@ -319,7 +319,7 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p
   p->off_tile_expert = take((size_t)p->max_tiles * 4);
   p->off_tile_row0 = take((size_t)p->max_tiles * 4);
   p->off_h = take((size_t)p->max_slots * F * dtype_size(dt));
-  p->off_slot_out = take((size_t)p->max_slots * H * 4);
+  p->off_slot_out = take(with_slot_out ? (size_t)p->max_slots * H * 4 : 0);
   p->total = off > 0 ? off : 256;
   return MOEP_OK;
 }
@@ -365,12 +365,13 @@ int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_ma
 
 
 int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta,
-                             int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s) {
+                             int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s, int32_t* pos_out) {
   const int64_t T = p.T;
   const int K = p.ks;
-  int32_t* pos = (int32_t*)(ws + p.off_pos);
-  int32_t* topk = topk_out ? topk_out : pos + (int64_t)K * T;
-  float* tw = (float*)(pos + 2 * (int64_t)K * T);
+  int32_t* ws_pos = (int32_t*)(ws + p.off_pos);
+  int32_t* pos = pos_out ? pos_out : ws_pos;
+  int32_t* topk = topk_out ? topk_out : ws_pos + (int64_t)K * T;
+  float* tw = (float*)(ws_pos + 2 * (int64_t)K * T);
   int32_t* counts = (int32_t*)(ws + p.off_counts);
   const int64_t n_blocks = ceil_div(T, RB);
   int32_t* slot_token = (int32_t*)(ws + p.off_slot_token);

@@ -529,3 +529,83 @@ def test_frequency_baseline_is_scored_by_the_enumeration():
     l64 = logits_t.cpu().numpy().astype(np.float64)
     ref = oracle.pruned_layer_output(l64, wl.to_f64(Y_t), kept, 2) - oracle.layer_output(l64, wl.to_f64(Y_t), 2)
     assert loss[idx] == pytest.approx(float((ref ** 2).sum()), rel=LOSS_RTOL)
+
+
+# ------------------------------------------------------------------ rank-limited expert pass
+def densify(ranked, E, T):
+    """Full [E,T,H] fp64 array from the ranked outputs, zeros where an expert was not run."""
+    logits_t, experts_t, slot_t, Yr_t = ranked
+    Yr = wl.to_f64(Yr_t)
+    experts, slot = experts_t.cpu().numpy(), slot_t.cpu().numpy()
+    Y = np.zeros((E, T, Yr.shape[1]))
+    for j in range(experts.shape[1]):
+        Y[experts[:, j], np.arange(T)] = Yr[slot[:, j]]
+    return Y
+
+
+@pytest.mark.parametrize("dtype,E,H,F,T,k,rs,n_rank", [
+    ("bf16", 8, 256, 512, 1100, 2, (6, 4), 6),         # the benchmark's pair of r from one pass
+    ("bf16", 8, 128, 256, 700, 2, (6,), 4),            # exactly n_act ranks
+    ("bf16", 8, 128, 256, 300, 2, (7, 5, 3), 8),       # every expert: same work as the dense pass
+    ("f32", 6, 64, 128, 400, 2, (4, 3), 5),
+    ("bf16", 5, 128, 192, 3, 3, (4,), 4),              # fewer tokens than experts: empty segments
+    ("bf16", 16, 128, 256, 600, 4, (14,), 6),          # 16 experts, top-4
+])
+def test_rank_limited_pass_matches_dense_pass_and_oracle(dtype, E, H, F, T, k, rs, n_rank):
+    cfg, layer = small_layer(dtype, E, k, H, F, T, index=15)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    logits_d, Y_d = pkg.moe_expert_outputs(*ws)
+    ranked = pkg.moe_expert_outputs_ranked(*ws, n_rank)
+    torch.cuda.synchronize()
+    logits_t, experts_t, slot_t, Yr_t = ranked
+    assert torch.equal(logits_t, logits_d)
+    lg = logits_t.cpu().numpy()
+    experts, slot = experts_t.cpu().numpy(), slot_t.cpu().numpy()
+    assert np.array_equal(experts, oracle.routing_order(lg)[:, :n_rank])
+    # slots: a permutation of 0 .. T n_rank - 1, grouped by expert, ascending token inside an expert
+    flat = slot.reshape(-1)
+    assert np.array_equal(np.sort(flat), np.arange(T * n_rank))
+    by_slot_expert = np.empty(T * n_rank, dtype=np.int64)
+    by_slot_token = np.empty(T * n_rank, dtype=np.int64)
+    by_slot_expert[flat] = experts.reshape(-1)
+    by_slot_token[flat] = np.repeat(np.arange(T), n_rank)
+    assert np.all(np.diff(by_slot_expert) >= 0)
+    same = np.diff(by_slot_expert) == 0
+    assert np.all(np.diff(by_slot_token)[same] > 0)
+    # each stored row is the dense pass's row, bit for bit (same K loop, same epilogue)
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    tok = torch.arange(T, device=DEV)
+    for j in range(n_rank):
+        dense_rows = Y_d[experts_t[:, j].long(), tok]
+        assert torch.equal(Yr_t[slot_t[:, j].long()].view(bits), dense_rows.view(bits))
+    Yfull = densify(ranked, E, T)
+    l64 = lg.astype(np.float64)
+    for r in rs:
+        loss_t, amin_t, amask_t, unaff_t = pkg.prune_enumerate_ranked(logits_t, experts_t, slot_t, Yr_t, k, r)
+        dl, da, dm, du = pkg.prune_enumerate(logits_d, Y_d, k, r)
+        torch.cuda.synchronize()
+        loss = loss_t.cpu().numpy().astype(np.float64)
+        ref, _, _ = oracle.prune_enumerate(l64, Yfull, k, r)
+        check_losses(loss, ref)
+        check_argmin(int(amin_t.item()), ref, loss)
+        np.testing.assert_allclose(loss, dl.cpu().numpy().astype(np.float64), rtol=1e-5, atol=0)
+        assert int(amin_t.item()) == int(da.item()) and int(amask_t.item()) == int(dm.item())
+        assert int(unaff_t.item()) == int(du.item())
+
+
+def test_rank_limited_pass_argument_checks():
+    cfg, layer = small_layer("bf16", 8, 2, 128, 256, 64, index=15)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    ranked = pkg.moe_expert_outputs_ranked(*ws, 4)
+    torch.cuda.synchronize()
+    with pytest.raises(pkg.MoepError) as ei:               # r = 4 can reach rank 6 > n_rank = 4
+        pkg.prune_enumerate_ranked(*ranked, 2, 4)
+    assert ei.value.status == 1
+    with pytest.raises(pkg.MoepError) as ei:
+        pkg.moe_expert_outputs_ranked(*ws, 9)
+    assert ei.value.status == 1
+    empty = pkg.moe_expert_outputs_ranked(d["x"][:0].contiguous(), *ws[1:], 4)
+    torch.cuda.synchronize()
+    assert empty[3].shape == (0, 128)
