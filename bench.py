@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--workload", default="C3", choices=["C2", "C3"],
                     help="C3 = Mixtral-shaped layer (the headline); C2 = mid layer (quick check)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-rank-limited", action="store_true",
+                    help="skip the extra, separately timed leg that redoes expert outputs + enumeration with "
+                         "the rank-limited expert pass")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the timed region, so that a "
                          "rocprofv3 --pmc run of this command holds a kernel of known traffic to scale "
@@ -119,12 +122,10 @@ def main():
     ws_skip = torch.empty(binding.moe_forward_skip_workspace(T_skip, E, H, F, dt), dtype=torch.uint8, device=dev)
     x_skip = x[:T_skip]
 
-    # beta = median of w_e1 / w_e0 over the skip batch (Sec. 3.3), from a router pass done up front.
+    # beta = median of w_e1 / w_e0 over the skip batch (Sec. 3.3), calibrated on the device up front.
     _, _, lg, _ = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip)
-    top = torch.topk(lg.double(), 2, dim=1).values
-    beta = float(torch.exp(top[:, 1] - top[:, 0]).median().item()) if T_skip % 2 else \
-        float(torch.exp(top[:, 1] - top[:, 0]).sort().values[T_skip // 2 - 1:T_skip // 2 + 1].mean().item())
-    del lg, top
+    beta = float(pkg.skip_calibrate_beta(lg).item())
+    del lg
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -214,6 +215,62 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    # Extra leg, not part of `value`: the same forward with beta = 0 (nothing skipped), for the speedup
+    # dynamic skipping buys on this batch.
+    pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip, want_logits=False, want_top2=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip, want_logits=False, want_top2=False)
+    torch.cuda.synchronize()
+    unskipped_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, beta, workspace=ws_skip, want_logits=False, want_top2=False)
+    torch.cuda.synchronize()
+    skipped_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    out["skip_forward_vs_unskipped"] = {"tokens": T_skip, "unskipped_ms": unskipped_ms, "skipped_ms": skipped_ms,
+                                        "speedup": unskipped_ms / skipped_ms,
+                                        "unskipped_tokens_per_s": T_skip / (unskipped_ms * 1e-3),
+                                        "skipped_tokens_per_s": T_skip / (skipped_ms * 1e-3)}
+    if not args.no_rank_limited:
+        # Extra leg, timed on its own and NOT part of `value`: the same enumeration results from the
+        # rank-limited pass (each token through its n_rank best-ranked experts only).
+        n_rank = max(min(E, min(k, r) + E - r) for r in cfg.rs)
+        ws_rk = torch.empty(binding._lib.moe_expert_outputs_ranked_workspace(T, E, H, F, dt, n_rank),
+                            dtype=torch.uint8, device=dev)
+        rk_out = (logits, torch.empty((T, n_rank), dtype=torch.int32, device=dev),
+                  torch.empty((T, n_rank), dtype=torch.int32, device=dev),
+                  torch.empty((T * n_rank, H), dtype=torch.bfloat16, device=dev))
+        rk_res = {}
+
+        def ranked_step():
+            pkg.moe_expert_outputs_ranked(x, Wg, W1, W3, W2, n_rank, workspace=ws_rk, out=rk_out)
+            for r in cfg.rs:
+                rk_res[r] = pkg.prune_enumerate_ranked(*rk_out, k, r, workspace=ws_enum)
+
+        ranked_step()
+        torch.cuda.synchronize()
+        pkg.kernel_timing_enable(True)
+        pkg.kernel_timing_reset()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ranked_step()
+        torch.cuda.synchronize()
+        rk_elapsed = (time.perf_counter() - t0) / args.steps
+        rk_timing = pkg.kernel_timing_collect()
+        pkg.kernel_timing_enable(False)
+        rk_gemm_ms = sum(rk_timing[n][0] for n in ("gemm_gate_up_swiglu_routed", "gemm_down_routed")) / args.steps
+        out["rank_limited"] = {
+            "n_rank": n_rank, "ms_per_pass": 1e3 * rk_elapsed,
+            "dense_ms_per_pass": gemm_ms + enum_ms,
+            "expert_gemm_ms": rk_gemm_ms,
+            "expert_gemm_tflops": 6.0 * T * n_rank * H * F / (rk_gemm_ms * 1e-3) / 1e12,
+            "subset_tokens_per_s_with_skip_leg": n_sub * T / (rk_elapsed + skip_ms * 1e-3),
+            "same_argmin": all(int(rk_res[r][1].item()) == int(results[r][1].item()) for r in cfg.rs),
+            "kernels_ms": {n: v[0] / v[1] for n, v in sorted(rk_timing.items())},
+        }
+        del ws_rk, rk_out
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layer, Y, logits, torch, wl)
     print(json.dumps(out))
