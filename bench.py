@@ -94,7 +94,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over tokens with one small all-reduce, see DESIGN.md).", file=sys.stderr)
+              "(the path would shard over tokens with one small all-reduce of the loss vector).", file=sys.stderr)
         sys.exit(2)
     import torch
 
