@@ -270,6 +270,7 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
   up.tile_row0 = (const int32_t*)(w + p.off_tile_row0);
   up.seg_end = (const int32_t*)(w + p.off_seg_end);
   up.max_m_tiles = p.max_tiles;
+  up.tiles_in_use = up.tile_expert + p.max_tiles;
   if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu_routed")) return st;
 
   GemmArgs down;                    // slot_out[slot] = weight(slot) * h[slot] W2[e]^T, fp32
@@ -281,6 +282,7 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
   down.row_scale = plain_out ? nullptr : (const float*)(w + p.off_slot_scale);
   down.tile_expert = up.tile_expert; down.tile_row0 = up.tile_row0; down.seg_end = up.seg_end;
   down.max_m_tiles = p.max_tiles;
+  down.tiles_in_use = up.tiles_in_use;
   return run_gemm(down, dt, s, "gemm_down_routed");
 }
 

@@ -61,6 +61,7 @@ struct GemmArgs {
   const int32_t* seg_end = nullptr;     // [E] end row (exclusive) of each expert's segment
   int64_t b_expert_stride = 0;          // elements between consecutive experts' weights
   int64_t max_m_tiles = 0;              // grouped: number of entries in tile_expert/tile_row0
+  const int32_t* tiles_in_use = nullptr; // grouped, optional: device count of leading entries that hold work
 };
 
 constexpr int GEMM_BM = 256;   // rows per tile of either GEMM implementation's grouped map

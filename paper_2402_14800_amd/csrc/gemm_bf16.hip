@@ -53,6 +53,7 @@ struct KArgs {
   void* C;
   const float* row_scale;
   const int32_t* tile_expert; const int32_t* tile_row0; const int32_t* seg_end;
+  const int32_t* tiles_in_use;
   int64_t M, ldc;
   uint32_t lda_chunks, ldb_chunks;   // leading dimensions in 16-byte chunks
   int64_t b_expert_chunks;           // expert stride of B in 16-byte chunks
@@ -70,8 +71,12 @@ void gemm_bf16_kernel(KArgs p) {
   const int wm = wave >> 2, wn = wave & 3;
 
   // ---- which tile -------------------------------------------------------------
-  const uint32_t nblk = gridDim.x;
+  // Grouped launches are sized for the largest possible tile map; only its leading entries hold work.
+  // Spreading just those over the XCDs keeps every XCD busy (the launch's surplus workgroups leave here).
+  const uint32_t m_tiles = p.tiles_in_use ? (uint32_t)*p.tiles_in_use : (uint32_t)p.m_tiles;
+  const uint32_t nblk = p.tiles_in_use ? m_tiles * (uint32_t)p.n_tiles : gridDim.x;
   uint32_t bid = blockIdx.x;
+  if (bid >= nblk) return;
   {  // XCD-aware remap: ids i, i+8, i+16, ... run on XCD i % 8; give each XCD a contiguous run.
     const uint32_t per = nblk >> 3, rem = nblk & 7;
     const uint32_t xcd = bid & 7, j = bid >> 3;
@@ -81,7 +86,7 @@ void gemm_bf16_kernel(KArgs p) {
   const uint32_t group_sz = GROUP_M * p.n_tiles;
   const uint32_t group = bid / group_sz;
   const uint32_t first_m = group * GROUP_M;
-  const uint32_t gm = min((uint32_t)p.m_tiles - first_m, GROUP_M);
+  const uint32_t gm = min(m_tiles - first_m, GROUP_M);
   const uint32_t in_group = bid - group * group_sz;
   const int tm = first_m + in_group % gm;
   const int tn = in_group / gm;
@@ -287,6 +292,7 @@ int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name) {
   k.A = (const u32x4*)g.A; k.B0 = (const u32x4*)g.B0; k.B1 = (const u32x4*)g.B1;
   k.a_rows = g.a_rows; k.C = g.C; k.row_scale = g.row_scale;
   k.tile_expert = g.tile_expert; k.tile_row0 = g.tile_row0; k.seg_end = g.seg_end;
+  k.tiles_in_use = g.tile_expert ? g.tiles_in_use : nullptr;
   k.M = g.M; k.ldc = g.ldc;
   k.lda_chunks = (uint32_t)(g.lda / 8); k.ldb_chunks = (uint32_t)(g.K / 8);
   k.b_expert_chunks = g.b_expert_stride / 8;

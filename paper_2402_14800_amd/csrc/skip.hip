@@ -6,7 +6,8 @@
 //            a0 = 1 / (1 + rho), a1 = rho / (1 + rho), rho = exp(delta); a0 = 1 when skipped.
 //            Also counts, per block of 256 tokens, the rows each expert receives.
 //   scan     turns the counts into each (block, expert)'s first slot, each expert's segment end,
-//            and the map from 256-row M tiles to (expert, first row) that the grouped GEMMs walk.
+//            and the map from 256-row M tiles to (expert, first row) that the grouped GEMMs walk
+//            (entry [max_tiles] of the expert list holds the number of tiles in use).
 //   scatter  writes slot -> token and slot -> weight lists and token -> slot positions.  Within an
 //            expert's segment the rows are in ascending token order, so the result is reproducible.
 //   combine  out[t] = slot_out[pos0] (+ slot_out[pos1] unless skipped); the down projection has
@@ -85,6 +86,7 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ counts,
         ++idx;
       }
     n_tiles = idx;
+    tile_expert[max_tiles] = idx;          // number of tiles in use, read by the grouped GEMMs
   }
   __syncthreads();
   if (e < E) {
@@ -316,7 +318,7 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p
   p->off_pos = take((size_t)T * ks * 4 * 3);           // pos, experts, weights: [T,ks] each
   p->off_counts = take((size_t)n_blocks * E * 4);
   p->off_seg_end = take((size_t)E * 4);
-  p->off_tile_expert = take((size_t)p->max_tiles * 4);
+  p->off_tile_expert = take((size_t)(p->max_tiles + 1) * 4);   // + the count of tiles in use
   p->off_tile_row0 = take((size_t)p->max_tiles * 4);
   p->off_h = take((size_t)p->max_slots * F * dtype_size(dt));
   p->off_slot_out = take(with_slot_out ? (size_t)p->max_slots * H * 4 : 0);
