@@ -23,7 +23,8 @@
 //
 // Workgroup order: consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with a
 // private L2.  Ids are remapped so that every XCD works on a contiguous run of tiles, ordered
-// 8 M-tiles deep before moving along N, so that the tiles in flight on one XCD share operand panels.
+// 8 (gate/up) or 4 (down) M-tiles deep before moving along N, so that the 32 tiles in flight on one
+// XCD share operand panels.
 #include "common.h"
 
 namespace moep {
@@ -82,7 +83,7 @@ void gemm_bf16_kernel(KArgs p) {
     const uint32_t xcd = bid & 7, j = bid >> 3;
     bid = xcd * per + (xcd < rem ? xcd : rem) + j;
   }
-  constexpr uint32_t GROUP_M = 8;
+  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;   // measured: the long-K down projection prefers 4 x 8 tiles per XCD
   const uint32_t group_sz = GROUP_M * p.n_tiles;
   const uint32_t group = bid / group_sz;
   const uint32_t first_m = group * GROUP_M;
