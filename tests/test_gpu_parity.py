@@ -609,3 +609,48 @@ def test_rank_limited_pass_argument_checks():
     empty = pkg.moe_expert_outputs_ranked(d["x"][:0].contiguous(), *ws[1:], 4)
     torch.cuda.synchronize()
     assert empty[3].shape == (0, 128)
+
+
+# ------------------------------------------------------------------ HIP graph replay
+def test_enumeration_and_skip_forward_replay_in_a_hip_graph():
+    """The entry points allocate nothing and enqueue only kernels, so a caller can capture them.
+    Every replay (with the program's own eager work and synchronisations in between) must give
+    the bits of the eager call on the same inputs."""
+    E, k, r, T, H, F = 8, 2, 6, 700, 128, 256
+    cfg, layer = small_layer("bf16", E, k, H, F, T, index=16)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    logits0, Y0 = pkg.moe_expert_outputs(*ws)
+    torch.cuda.synchronize()
+    from paper_2402_14800_amd import binding
+    dt = binding.MOEP_BF16
+    ws_enum = torch.empty(binding.prune_enumerate_workspace(T, E, H, k, r, dt), dtype=torch.uint8, device=DEV)
+    ws_skip = torch.empty(binding.moe_forward_skip_workspace(T, E, H, F, dt), dtype=torch.uint8, device=DEV)
+    s_logits, s_Y, s_x = logits0.clone(), Y0.clone(), d["x"].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                    # warm-up on the side stream, as torch asks before capture
+        pkg.prune_enumerate(s_logits, s_Y, k, r, workspace=ws_enum)
+        pkg.moe_forward_skip(s_x, *ws[1:], 0.5, workspace=ws_skip)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g_loss, g_amin, g_amask, g_unaff = pkg.prune_enumerate(s_logits, s_Y, k, r, workspace=ws_enum)
+        g_out, g_skip, _, _ = pkg.moe_forward_skip(s_x, *ws[1:], 0.5, workspace=ws_skip,
+                                                   want_logits=False, want_top2=False)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99)
+    for trial in range(3):
+        new_logits = torch.randn((T, E), generator=gen, device=DEV)
+        new_Y = torch.randn((E, T, H), generator=gen, device=DEV).to(torch.bfloat16)
+        new_x = torch.randn((T, H), generator=gen, device=DEV).to(torch.bfloat16)
+        s_logits.copy_(new_logits); s_Y.copy_(new_Y); s_x.copy_(new_x)
+        graph.replay()
+        torch.cuda.synchronize()
+        e_loss, e_amin, e_amask, e_unaff = pkg.prune_enumerate(new_logits, new_Y, k, r)
+        e_out, e_skip, _, _ = pkg.moe_forward_skip(new_x, *ws[1:], 0.5)
+        torch.cuda.synchronize()
+        assert torch.equal(g_loss.view(torch.int32), e_loss.view(torch.int32)), trial
+        assert int(g_amin.item()) == int(e_amin.item()) and int(g_unaff.item()) == int(e_unaff.item())
+        assert torch.equal(g_skip, e_skip) and torch.equal(g_out.view(torch.int16), e_out.view(torch.int16)), trial
