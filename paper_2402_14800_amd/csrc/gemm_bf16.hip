@@ -146,12 +146,10 @@ void gemm_bf16_kernel(KArgs p) {
   }
 
   // ---- fragment addresses ---------------------------------------------------------
-  // MFMA 32x32x16: lane l supplies row (l & 31) and the 8 k-values 8 (l >> 5) .. + 7 of A,
-  // and the same for B (as [N,K]).  Per K step of 64 there are 4 such slices (kk): chunk
-  // 2 kk + (l >> 5) of the row, found at position chunk ^ swz(row); since swz only touches the
-  // chunk index, slice kk is at (address of slice 0) ^ (kk << 5).
-  // MFMA 16x16x32: lane l supplies row (l & 15) and the 8 k-values 8 (l >> 4) .. + 7; a K step of 64 is
-  // two slices: chunk 4 s + (l >> 4), at (address of slice 0) ^ (s << 6).
+  // MFMA 16x16x32: lane l supplies row (l & 15) and the 8 k-values 8 (l >> 4) .. + 7 of A, and the
+  // same for B (as [N,K]); a K step of 64 is two slices: chunk 4 s + (l >> 4) of the row, found at
+  // position chunk ^ swz(row); swz only touches the low chunk bits, so slice s is at
+  // (address of slice 0) ^ (s << 6).
   const int frow = lane & 15, fk = lane >> 4;
   int a_frag[8], b_frag[4];
 #pragma unroll
