@@ -654,3 +654,53 @@ def test_enumeration_and_skip_forward_replay_in_a_hip_graph():
         assert torch.equal(g_loss.view(torch.int32), e_loss.view(torch.int32)), trial
         assert int(g_amin.item()) == int(e_amin.item()) and int(g_unaff.item()) == int(e_unaff.item())
         assert torch.equal(g_skip, e_skip) and torch.equal(g_out.view(torch.int16), e_out.view(torch.int16)), trial
+
+
+# ------------------------------------------------------------------ widened entry points at full size
+def test_config2_rank_limited_and_topk_skip_full_size():
+    """Mid layer (config 2) through the rank-limited pass (sampled rows against the oracle, losses against
+    the dense pass and, on a token prefix, the oracle) and through the generalised skipping forward
+    (sampled tokens against the oracle)."""
+    cfg = wl.CONFIGS["C2"]
+    layer = wl.make_layer(cfg, device=DEV)
+    ws = [layer[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    E, k, T = cfg.E, cfg.k, cfg.T
+    n_rank = max(min(E, min(k, r) + E - r) for r in cfg.rs)
+    logits_d, Y_d = pkg.moe_expert_outputs(*ws)
+    ranked = pkg.moe_expert_outputs_ranked(*ws, n_rank)
+    torch.cuda.synchronize()
+    logits_t, experts_t, slot_t, Yr_t = ranked
+    assert torch.equal(logits_t, logits_d)
+    W64 = weights_f64(layer)
+    tokens = torch.tensor(np.random.default_rng(5).choice(T, 128, replace=False), device=DEV).sort().values
+    x64 = wl.to_f64(layer["x"][tokens])
+    _, ref_Y = oracle.expert_outputs(x64, wl.to_f64(layer["Wgate"]), W64["W1"], W64["W3"], W64["W2"])
+    ex = experts_t[tokens].cpu().numpy()
+    for j in range(n_rank):
+        got = wl.to_f64(Yr_t[slot_t[tokens, j].long()])
+        check_outputs(got, ref_Y[ex[:, j], np.arange(len(tokens))], f"ranked rows, rank {j}")
+    prefix = 2048
+    pre = pkg.moe_expert_outputs_ranked(*(w[:prefix].contiguous() if i == 0 else w for i, w in enumerate(ws)), n_rank)
+    torch.cuda.synchronize()
+    for r in cfg.rs:
+        lr, ar, mr, ur = pkg.prune_enumerate_ranked(logits_t, experts_t, slot_t, Yr_t, k, r)
+        ld, ad, md, ud = pkg.prune_enumerate(logits_d, Y_d, k, r)
+        lp, ap, _, _ = pkg.prune_enumerate_ranked(*pre, k, r)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(lr.cpu().numpy(), ld.cpu().numpy(), rtol=1e-5)
+        assert int(ar.item()) == int(ad.item()) and int(mr.item()) == int(md.item()) and int(ur.item()) == int(ud.item())
+        ref, _, _ = oracle.prune_enumerate(pre[0].cpu().numpy().astype(np.float64), densify(pre, E, prefix), k, r)
+        lp64 = lp.cpu().numpy().astype(np.float64)
+        check_losses(lp64, ref)
+        check_argmin(int(ap.item()), ref, lp64)
+    # generalised skipping, k = 4 of 8, on the whole batch; the oracle redoes sampled tokens
+    beta = float(np.float32(0.1))
+    out_t, n_used_t, lg_t, topk_t = pkg.moe_forward_skip_topk(*ws, 4, beta)
+    torch.cuda.synchronize()
+    ref_out, i_star, experts = oracle.forward_skip_topk(x64, wl.to_f64(layer["Wgate"]), W64["W1"], W64["W3"], W64["W2"],
+                                                        4, beta, logits=lg_t[tokens].cpu().numpy())
+    assert np.array_equal(n_used_t[tokens].cpu().numpy(), i_star)
+    assert np.array_equal(topk_t[tokens].cpu().numpy(), experts)
+    check_outputs(wl.to_f64(out_t[tokens]), ref_out, "top-k skip out (sampled tokens)")
+    hist = torch.bincount(n_used_t, minlength=5).cpu().numpy()
+    assert hist[0] == 0 and hist[1:].sum() == T and (hist[1:] > 0).sum() >= 3
