@@ -33,7 +33,8 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs of this script with --copy-calibration, each
 # scaled by what the 1 GiB copy reads on the same counter: x2.000 and x1.000); the figures are in
 # profiles/hot_path_C3_hbm_traffic.txt.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"C3": 98.7e9, "C2": None}
+MEASURED_TRAFFIC_BYTES = {"C3": 98.7e9, "C2": None, "C4": None}
+PEAK_ALU_LANE_OPS = 256 * 64 * 2.4e9   # CUs x lanes x clock: plain (non-packed) fp32/int lane operations per second
 
 
 def parse():
@@ -41,8 +42,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="C3", choices=["C2", "C3"],
-                    help="C3 = Mixtral-shaped layer (the headline); C2 = mid layer (quick check)")
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4"],
+                    help="C3 = Mixtral-shaped layer (the headline); C2 = mid layer (quick check); "
+                         "C4 = enumeration stress (16 experts, top-4, 12870 + 1820 subsets; no skip leg)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rank-limited", action="store_true",
                     help="skip the extra, separately timed leg that redoes expert outputs + enumeration with "
@@ -66,7 +68,9 @@ def cpu_baseline(cfg, layer, Y, logits, torch, wl):
     except Exception:
         cores = os.cpu_count() or 1
     n1 = 128 if cfg.H >= 4096 else 512          # tokens through all E experts (fp64 GEMMs)
-    n2 = 2048 if cfg.H >= 4096 else 4096        # tokens through the enumeration, all r
+    n_sub_all = sum(math.comb(cfg.E, r) for r in cfg.rs)
+    # tokens through the enumeration, all r: bounded so that the oracle needs some ten seconds
+    n2 = min(2048 if cfg.H >= 4096 else 4096, max(32, int(6e5 / n_sub_all)))
     x = wl.to_f64(layer["x"][:n1])
     Wg = wl.to_f64(layer["Wgate"])
     t_o1 = 0.0
@@ -108,6 +112,7 @@ def main():
     dev = torch.device("cuda:0")
     cfg = wl.CONFIGS[args.workload]
     T_skip = min(32768, cfg.T)
+    do_skip = cfg.k == 2                               # the top-2 skipping forward is defined for k = 2
     layer = wl.make_layer(cfg, device=dev)            # torch generator on the device
     x, Wg, W1, W3, W2 = (layer[n] for n in ("x", "Wgate", "W1", "W3", "W2"))
     E, H, F, T, k = cfg.E, cfg.H, cfg.F, cfg.T, cfg.k
@@ -119,13 +124,16 @@ def main():
     ws_exp = torch.empty(binding.moe_expert_outputs_workspace(T, E, H, F, dt), dtype=torch.uint8, device=dev)
     ws_enum = torch.empty(max(binding.prune_enumerate_workspace(T, E, H, k, r, dt) for r in cfg.rs),
                           dtype=torch.uint8, device=dev)
-    ws_skip = torch.empty(binding.moe_forward_skip_workspace(T_skip, E, H, F, dt), dtype=torch.uint8, device=dev)
     x_skip = x[:T_skip]
-
-    # beta = median of w_e1 / w_e0 over the skip batch (Sec. 3.3), calibrated on the device up front.
-    _, _, lg, _ = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip)
-    beta = float(pkg.skip_calibrate_beta(lg).item())
-    del lg
+    beta = None
+    if do_skip:
+        ws_skip = torch.empty(binding.moe_forward_skip_workspace(T_skip, E, H, F, dt), dtype=torch.uint8, device=dev)
+        # beta = median of w_e1 / w_e0 over the skip batch (Sec. 3.3), calibrated on the device up front.
+        _, _, lg, _ = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip)
+        beta = float(pkg.skip_calibrate_beta(lg).item())
+        del lg
+    bias = layer.get("bias")                           # config 4: per-expert logit bias, added by the harness
+    logits_b = torch.empty_like(logits) if bias is not None else logits
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -138,10 +146,13 @@ def main():
 
     def step():
         pkg.moe_expert_outputs(x, Wg, W1, W3, W2, logits=logits, Y=Y, workspace=ws_exp)
+        if bias is not None:
+            torch.add(logits, bias, out=logits_b)
         for r in cfg.rs:
-            results[r] = pkg.prune_enumerate(logits, Y, k, r, workspace=ws_enum)
-        results["skip"] = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, beta, workspace=ws_skip,
-                                               want_logits=False, want_top2=False)
+            results[r] = pkg.prune_enumerate(logits_b, Y, k, r, workspace=ws_enum)
+        if do_skip:
+            results["skip"] = pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, beta, workspace=ws_skip,
+                                                   want_logits=False, want_top2=False)
 
     for _ in range(args.warmup):
         step()
@@ -163,13 +174,19 @@ def main():
 
     # ---- per-kernel figures: algorithmic work per launch / measured launch time ----
     es = 2
-    slots = float(2 * T_skip - int(results["skip"][1].sum().item()))
+    slots = float(2 * T_skip - int(results["skip"][1].sum().item())) if do_skip else 0.0
+    # scorer: selection steps and multiply-adds per (subset, token) pair, summed over the r of this workload
+    def pair_ops(r):
+        n_act = min(E, min(k, r) + E - r)
+        return 4 * n_act + n_act * (n_act + 3) // 2 + 8
+    score_ops = float(sum(math.comb(E, r) * T * pair_ops(r) for r in cfg.rs))
     work = {   # kernel -> (bound, algorithmic flops or bytes per launch)
         "gemm_gate_up_swiglu": ("mfma", 4.0 * T * H * F),
         "gemm_down": ("mfma", 2.0 * T * H * F),
         "gemm_gate_up_swiglu_routed": ("mfma", 4.0 * slots * H * F),
         "gemm_down_routed": ("mfma", 2.0 * slots * H * F),
         "gram": ("hbm", float(E) * T * H * es + 4.0 * T * E * E),
+        "subset_score": ("alu", score_ops / len(cfg.rs)),     # per launch, averaged over the r of this workload
         "router_logits": ("hbm", None),      # launched with two different T: reported as time only
     }
     kernels = {}
@@ -178,7 +195,10 @@ def main():
         entry = {"launches_per_step": n / args.steps, "avg_ms": avg_ms}
         bound, w = work.get(name, (None, None))
         if w:
-            if bound == "mfma":
+            if bound == "alu":
+                a = w / (avg_ms * 1e-3)
+                entry.update(bound="alu", achieved=a, peak=PEAK_ALU_LANE_OPS, unit="lane-op/s", frac=a / PEAK_ALU_LANE_OPS)
+            elif bound == "mfma":
                 a = w / (avg_ms * 1e-3) / 1e12
                 entry.update(bound="mfma", achieved=a, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s",
                              frac=a / PEAK_MFMA_BF16_TFLOPS)
@@ -197,12 +217,14 @@ def main():
     skip_names = ("gemm_gate_up_swiglu_routed", "gemm_down_routed", "skip_route_dispatch", "skip_combine")
     skip_ms = sum(timing[n][0] for n in skip_names if n in timing) / args.steps
     out = {
-        "metric": "subset·tokens scored/sec (whole hot path: expert outputs + enumeration r=6,4 + skip forward)",
+        "metric": "subset·tokens scored/sec (whole hot path: expert outputs + enumeration for every r"
+                  + (" + skip forward)" if do_skip else ")"),
         "value": value, "unit": "subset·tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: E={E} top-{k} H={H} F={F} T={T} r={list(cfg.rs)}; "
-                               f"skip forward on {T_skip} tokens, beta={beta:.4f}",
+                               + (f"skip forward on {T_skip} tokens, beta={beta:.4f}" if do_skip else
+                                  f"logit bias variance {cfg.gate_bias_var}"),
                    "input_backend": layer["backend"], "seed": cfg.seed},
         "expert_gemm_tflops": 6.0 * T * H * F * E / (gemm_ms * 1e-3) / 1e12,
         "expert_gemm_ms": gemm_ms,
@@ -210,33 +232,37 @@ def main():
         "enumerate_ms": enum_ms,
         "skip_forward_tokens_per_s": T_skip / (skip_ms * 1e-3) if skip_ms else None,
         "skip_forward_ms": skip_ms,
-        "skip_fraction": 1.0 - (slots - T_skip) / T_skip,
+        "skip_fraction": 1.0 - (slots - T_skip) / T_skip if do_skip else None,
         "argmin": {str(r): int(results[r][1].item()) for r in cfg.rs},
         "roofline": roofline,
         "kernels": kernels,
     }
     # Extra leg, not part of `value`: the same forward with beta = 0 (nothing skipped), for the speedup
     # dynamic skipping buys on this batch.
-    pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip, want_logits=False, want_top2=False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, 0.0, workspace=ws_skip, want_logits=False, want_top2=False)
-    torch.cuda.synchronize()
-    unskipped_ms = 1e3 * (time.perf_counter() - t0) / args.steps
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, beta, workspace=ws_skip, want_logits=False, want_top2=False)
-    torch.cuda.synchronize()
-    skipped_ms = 1e3 * (time.perf_counter() - t0) / args.steps
-    out["skip_forward_vs_unskipped"] = {"tokens": T_skip, "unskipped_ms": unskipped_ms, "skipped_ms": skipped_ms,
-                                        "speedup": unskipped_ms / skipped_ms,
-                                        "unskipped_tokens_per_s": T_skip / (unskipped_ms * 1e-3),
-                                        "skipped_tokens_per_s": T_skip / (skipped_ms * 1e-3)}
-    if not args.no_rank_limited:
+    if do_skip:
+        def forward(b):
+            pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, b, workspace=ws_skip, want_logits=False, want_top2=False)
+
+        def timed_forward(b):
+            forward(b)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                forward(b)
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0) / args.steps
+
+        unskipped_ms = timed_forward(0.0)
+        skipped_ms = timed_forward(beta)
+        out["skip_forward_vs_unskipped"] = {"tokens": T_skip, "unskipped_ms": unskipped_ms, "skipped_ms": skipped_ms,
+                                            "speedup": unskipped_ms / skipped_ms,
+                                            "unskipped_tokens_per_s": T_skip / (unskipped_ms * 1e-3),
+                                            "skipped_tokens_per_s": T_skip / (skipped_ms * 1e-3)}
+    n_rank_needed = max(min(E, min(k, r) + E - r) for r in cfg.rs)
+    if not args.no_rank_limited and n_rank_needed <= 8:
         # Extra leg, timed on its own and NOT part of `value`: the same enumeration results from the
         # rank-limited pass (each token through its n_rank best-ranked experts only).
-        n_rank = max(min(E, min(k, r) + E - r) for r in cfg.rs)
+        n_rank = n_rank_needed
         ws_rk = torch.empty(binding._lib.moe_expert_outputs_ranked_workspace(T, E, H, F, dt, n_rank),
                             dtype=torch.uint8, device=dev)
         rk_out = (logits, torch.empty((T, n_rank), dtype=torch.int32, device=dev),
@@ -272,7 +298,7 @@ def main():
         }
         del ws_rk, rk_out
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, layer, Y, logits, torch, wl)
+        out["cpu_baseline"] = cpu_baseline(cfg, layer, Y, logits_b, torch, wl)
     print(json.dumps(out))
 
 
