@@ -259,7 +259,8 @@ def main():
                                             "unskipped_tokens_per_s": T_skip / (unskipped_ms * 1e-3),
                                             "skipped_tokens_per_s": T_skip / (skipped_ms * 1e-3)}
     n_rank_needed = max(min(E, min(k, r) + E - r) for r in cfg.rs)
-    if not args.no_rank_limited and n_rank_needed <= 8:
+    # (not with a harness-side logit bias: the rank-limited pass ranks by its own router logits)
+    if not args.no_rank_limited and n_rank_needed <= 8 and bias is None:
         # Extra leg, timed on its own and NOT part of `value`: the same enumeration results from the
         # rank-limited pass (each token through its n_rank best-ranked experts only).
         n_rank = n_rank_needed
