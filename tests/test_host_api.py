@@ -148,3 +148,36 @@ def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(ImportError):
         binding._load()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_workload_generators_are_seeded_and_prefix_stable():
+    import numpy as np
+    import torch
+    from paper_2402_14800_amd import workloads as wl
+
+    cfg = wl.CONFIGS["C1"]
+    a, b = wl.make_layer(cfg), wl.make_layer(cfg)
+    for n in ("x", "Wgate", "W1", "W3", "W2"):
+        assert torch.equal(a[n], b[n]) and a[n].dtype == torch.float32
+    assert a["bias"] is None and a["backend"] == "numpy"
+    half = wl.make_layer(cfg.with_tokens(cfg.T // 2))
+    assert torch.equal(half["x"], a["x"][: cfg.T // 2])            # a smaller batch is a prefix
+    assert torch.equal(half["W1"], a["W1"])
+    other = wl.make_layer(wl.LayerConfig("other", 7, "bf16", E=4, k=2, H=64, F=128, T=512, rs=(2,), rms_norm=True,
+                                         gate_bias_var=0.5))
+    assert other["x"].dtype == torch.bfloat16 and other["bias"].shape == (4,)
+    rms = other["x"].float().pow(2).mean(dim=1).sqrt()
+    assert torch.allclose(rms, torch.ones_like(rms), atol=2e-2)     # unit-RMS rows, up to bf16 rounding
+    assert abs(float(a["W2"].std()) - 128 ** -0.5) < 0.01 and abs(float(a["Wgate"].std()) - 64 ** -0.5) < 0.02
+    assert wl.CONFIGS["C3"].seed == 20240214 + 2000 and wl.CONFIGS["C3"].T == 262144
+    lg, Y = wl.make_enumeration_inputs(6, 50, 32, dtype="bf16", seed=3, bias_var=0.5)
+    lg2, Y2 = wl.make_enumeration_inputs(6, 50, 32, dtype="bf16", seed=3, bias_var=0.5)
+    assert torch.equal(lg, lg2) and torch.equal(Y, Y2) and lg.dtype == torch.float32 and Y.dtype == torch.bfloat16
+    assert np.array_equal(wl.to_f64(Y).astype(np.float32), Y.float().numpy())
