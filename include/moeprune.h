@@ -18,6 +18,9 @@
  *   - All work is enqueued on `hip_stream` (a hipStream_t, NULL = the default
  *     stream) and the call returns without waiting for it; outputs are valid
  *     once the caller has synchronised the stream.
+ *   - Only kernels are enqueued (no memset, no memcpy, no allocation), so a call can be captured
+ *     into a HIP graph.  The first call that uses a GEMM kernel raises that kernel's dynamic
+ *     LDS limit (hipFuncSetAttribute): make one eager call of an entry point before capturing it.
  *   - Return value: a moep_status.  Nothing throws or aborts across the ABI.
  *     After a non-zero status moep_last_error() describes it.  Inputs holding
  *     NaN or Inf give unspecified results.
