@@ -104,7 +104,7 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
  * through its n_rank best-ranked experts only -- n_rank / E of the FLOPs of moe_expert_outputs --
  * and prune_enumerate_ranked scores the subsets from those outputs; the losses are the same real
  * numbers as prune_enumerate's whenever n_rank >= n_act.
- *   n_rank: 1 .. min(E, 8)
+ *   n_rank: 1 .. min(E, 16)
  *   logits [T,E] fp32 (out)
  *   ranked_experts [T,n_rank] int32 (out): the token's experts by descending logit, ties to the lower index
  *   slot_of [T,n_rank] int32 (out): row of Yr holding the output of ranked_experts[t,j] on token t
@@ -154,7 +154,7 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
                             void* hip_stream);
 
 /* ---- moe_forward_skip_topk -------------------------------------------------- */
-/* Dynamic skipping for top-k routing, 1 <= k <= 8 (appendix on the theory of dynamic skipping).
+/* Dynamic skipping for top-k routing, 1 <= k <= 16 (appendix on the theory of dynamic skipping).
  * Per token, with w_1 >= ... >= w_k the Eq. 1 weights of its top-k experts among `kept_mask`
  * (ties to the lower index), the top-i* experts stay, where
  *     i* = min { i in 1..k : sum_{m>i} w_m <= beta * sum_{m<=k} w_m },

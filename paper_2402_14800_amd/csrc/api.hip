@@ -338,7 +338,7 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
 // ------------------------------------------------------------------ moe_forward_skip_topk
 size_t moe_forward_skip_topk_workspace(int64_t T, int E, int H, int F, moep_dtype dt, int k) {
   if (!valid_shape(T, E, H, F, dt, "moe_forward_skip_topk_workspace")) return 0;
-  if (k < 1 || k > 8) return 0;
+  if (k < 1 || k > 16) return 0;
   SkipPlan p;
   if (plan_skip(T, E, H, F, dt, k, &p)) return 0;
   return p.total;
@@ -352,7 +352,7 @@ int moe_forward_skip_topk(const void* x, const void* Wgate, const void* W1, cons
   const char* who = "moe_forward_skip_topk";
   if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
   if (k < 1) return fail(MOEP_EINVAL, "%s: k=%d must be at least 1", who, k);
-  if (k > 8) return fail(MOEP_EUNSUPPORTED, "%s: k=%d (at most 8 experts per token)", who, k);
+  if (k > 16) return fail(MOEP_EUNSUPPORTED, "%s: k=%d (at most 16 experts per token)", who, k);
   if (E < 32 && (kept_mask >> E)) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x has bits beyond expert %d", who, kept_mask, E - 1);
   if (__builtin_popcount(kept_mask) < k) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x keeps fewer than k=%d experts", who, kept_mask, k);
   if (!(beta >= 0.0f) || std::isinf(beta)) return fail(MOEP_EINVAL, "%s: beta must be finite and >= 0", who);
@@ -408,7 +408,7 @@ int expert_selection_stats(const float* logits, int64_t T, int E, int k, int r, 
 // ------------------------------------------------------------------ rank-limited expert pass
 size_t moe_expert_outputs_ranked_workspace(int64_t T, int E, int H, int F, moep_dtype dt, int n_rank) {
   if (!valid_shape(T, E, H, F, dt, "moe_expert_outputs_ranked_workspace")) return 0;
-  if (n_rank < 1 || n_rank > 8 || n_rank > E) return 0;
+  if (n_rank < 1 || n_rank > 16 || n_rank > E) return 0;
   SkipPlan p;
   if (plan_skip(T, E, H, F, dt, n_rank, &p, false)) return 0;
   return p.total;
@@ -421,7 +421,7 @@ int moe_expert_outputs_ranked(const void* x, const void* Wgate, const void* W1, 
   const char* who = "moe_expert_outputs_ranked";
   if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
   if (n_rank < 1 || n_rank > E) return fail(MOEP_EINVAL, "%s: n_rank=%d out of range 1..E", who, n_rank);
-  if (n_rank > 8) return fail(MOEP_EUNSUPPORTED, "%s: n_rank=%d (at most 8)", who, n_rank);
+  if (n_rank > 16) return fail(MOEP_EUNSUPPORTED, "%s: n_rank=%d (at most 16)", who, n_rank);
   if (int st = check_alignment(H, F, dt, who)) return st;
   if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
   if (T == 0) return MOEP_OK;

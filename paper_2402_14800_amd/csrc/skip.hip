@@ -387,7 +387,9 @@ int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t ke
   switch (K) {
     MOEP_ROUTE_CASE(1) MOEP_ROUTE_CASE(2) MOEP_ROUTE_CASE(3) MOEP_ROUTE_CASE(4)
     MOEP_ROUTE_CASE(5) MOEP_ROUTE_CASE(6) MOEP_ROUTE_CASE(7) MOEP_ROUTE_CASE(8)
-    default: return fail(MOEP_EUNSUPPORTED, "moe_forward_skip_topk: k=%d (1..8)", K);
+    MOEP_ROUTE_CASE(9) MOEP_ROUTE_CASE(10) MOEP_ROUTE_CASE(11) MOEP_ROUTE_CASE(12)
+    MOEP_ROUTE_CASE(13) MOEP_ROUTE_CASE(14) MOEP_ROUTE_CASE(15) MOEP_ROUTE_CASE(16)
+    default: return fail(MOEP_EUNSUPPORTED, "top-k routing: k=%d (1..16)", K);
   }
 #undef MOEP_ROUTE_CASE
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, counts, n_blocks, p.E,
@@ -401,6 +403,8 @@ int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t ke
   switch (K) {
     MOEP_SCATTER_CASE(1) MOEP_SCATTER_CASE(2) MOEP_SCATTER_CASE(3) MOEP_SCATTER_CASE(4)
     MOEP_SCATTER_CASE(5) MOEP_SCATTER_CASE(6) MOEP_SCATTER_CASE(7) MOEP_SCATTER_CASE(8)
+    MOEP_SCATTER_CASE(9) MOEP_SCATTER_CASE(10) MOEP_SCATTER_CASE(11) MOEP_SCATTER_CASE(12)
+    MOEP_SCATTER_CASE(13) MOEP_SCATTER_CASE(14) MOEP_SCATTER_CASE(15) MOEP_SCATTER_CASE(16)
   }
 #undef MOEP_SCATTER_CASE
   MOEP_HIP(hipGetLastError());

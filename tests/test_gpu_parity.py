@@ -415,6 +415,7 @@ TOPK_CASES = [
     ("bf16", 8, 128, 256, 300, 1, 0.5, None),          # top-1: nothing to skip
     ("bf16", 8, 128, 256, 300, 4, 0.0, None),          # never skip: Eq. 2 with k = 4
     ("bf16", 8, 128, 256, 300, 4, 1.0, (1, 2, 4, 6, 7)),   # always down to the best kept expert
+    ("bf16", 16, 128, 256, 400, 12, 0.02, None),       # wide top-k
 ]
 
 
@@ -550,6 +551,7 @@ def densify(ranked, E, T):
     ("f32", 6, 64, 128, 400, 2, (4, 3), 5),
     ("bf16", 5, 128, 192, 3, 3, (4,), 4),              # fewer tokens than experts: empty segments
     ("bf16", 16, 128, 256, 600, 4, (14,), 6),          # 16 experts, top-4
+    ("bf16", 16, 128, 256, 500, 4, (8, 12), 12),       # the stress configuration's E, k, r: 12 ranks reach every subset
 ])
 def test_rank_limited_pass_matches_dense_pass_and_oracle(dtype, E, H, F, T, k, rs, n_rank):
     cfg, layer = small_layer(dtype, E, k, H, F, T, index=15)
@@ -604,7 +606,7 @@ def test_rank_limited_pass_argument_checks():
         pkg.prune_enumerate_ranked(*ranked, 2, 4)
     assert ei.value.status == 1
     with pytest.raises(pkg.MoepError) as ei:
-        pkg.moe_expert_outputs_ranked(*ws, 9)
+        pkg.moe_expert_outputs_ranked(*ws, 9)              # more ranks than experts
     assert ei.value.status == 1
     empty = pkg.moe_expert_outputs_ranked(d["x"][:0].contiguous(), *ws[1:], 4)
     torch.cuda.synchronize()

@@ -109,14 +109,14 @@ def test_argument_errors_come_back_as_status_codes():
     assert fp(*pargs(0b11, k=3)) == 2
     ft = binding._lib.moe_forward_skip_topk
     assert ft(*pargs(0xff, k=0)) == 1
-    assert ft(*pargs(0xff, k=9)) == 2
+    assert ft(*pargs(0xff, k=17)) == 2
     assert ft(*pargs(0b111, k=4)) == 1            # fewer kept experts than k
     assert ft(*pargs(0xff, k=4, beta=-1.0)) == 1
     assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 4) > \
         binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 2) > 0
     assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 2) == \
         binding._lib.moe_forward_skip_workspace(1024, 8, 64, 128, 1)
-    assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 9) == 0
+    assert binding._lib.moe_forward_skip_topk_workspace(1024, 8, 64, 128, 1, 17) == 0
     cal = binding._lib.skip_calibrate_beta
     cargs = lambda **kw: [one, kw.get("T", 64), kw.get("E", 8), ctypes.c_uint32(kw.get("mask", 0xff)), one, one,
                           kw.get("ws", 1 << 40), None]
