@@ -191,6 +191,9 @@ int moep_timing_collect(const char** names, double* total_ms, int64_t* launches,
 // ------------------------------------------------------------------ moe_expert_outputs
 size_t moe_expert_outputs_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {
   if (!valid_shape(T, E, H, F, dt, "moe_expert_outputs_workspace")) return 0;
+  if (dt == MOEP_BF16)   // packed h, packed x, one expert's packed W1/W3 pair and packed W2
+    return align256(packed_a_bytes(T, F)) + align256(packed_a_bytes(T, H)) +
+           align256(packed_b_bytes(F, H, true)) + align256(packed_b_bytes(H, F, false));
   return align256((size_t)T * (size_t)F * dtype_size(dt));
 }
 
@@ -208,6 +211,29 @@ int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const v
   const size_t es = dtype_size(dt);
 
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
+  if (dt == MOEP_BF16) {
+    // Operands are packed once (x) or once per expert (weights) into the blocked layout of the packed
+    // GEMM; h stays in that layout between the two projections and never exists row-major.
+    char* hp = (char*)ws;
+    char* xp = hp + align256(packed_a_bytes(T, F));
+    char* wgu = xp + align256(packed_a_bytes(T, H));
+    char* wdn = wgu + align256(packed_b_bytes(F, H, true));
+    if (int st = launch_pack_a_bf16(x, H, T, H, xp, s, "pack_x")) return st;
+    for (int e = 0; e < E; ++e) {
+      if (int st = launch_pack_b_bf16((const char*)W1 + (size_t)e * F * H * es, (const char*)W3 + (size_t)e * F * H * es,
+                                      F, H, wgu, s, "pack_w")) return st;
+      if (int st = launch_pack_b_bf16((const char*)W2 + (size_t)e * H * F * es, nullptr, H, F, wdn, s, "pack_w")) return st;
+      PackedGemmArgs up;                          // h = silu(x W1[e]^T) * (x W3[e]^T)
+      up.A = xp; up.B = wgu; up.C = hp;
+      up.M = T; up.N = F; up.K = H; up.epilogue = EPI_SWIGLU;
+      if (int st = launch_gemm_bf16_packed(up, s, "gemm_gate_up_swiglu")) return st;
+      PackedGemmArgs down;                        // Y[e] = h W2[e]^T
+      down.A = hp; down.B = wdn; down.C = (char*)Y + (size_t)e * T * H * es; down.ldc = H;
+      down.M = T; down.N = H; down.K = F; down.epilogue = EPI_STORE;
+      if (int st = launch_gemm_bf16_packed(down, s, "gemm_down")) return st;
+    }
+    return MOEP_OK;
+  }
   for (int e = 0; e < E; ++e) {
     GemmArgs up;                                  // h = silu(x W1[e]^T) * (x W3[e]^T)
     up.A = x; up.lda = H;

@@ -69,6 +69,25 @@ constexpr int GEMM_BM = 256;   // rows per tile of either GEMM implementation's 
 int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name);
 int launch_gemm_f32(const GemmArgs& g, hipStream_t s, const char* name);
 
+// ---- bf16 GEMM on packed operands (dense expert pass) ---------------------------------
+// Operands are re-laid out once into 16 KB blocks of 256 rows x 32 k-values (the layout is described in
+// gemm_bf16_packed.hip); EPI_SWIGLU writes its result as a packed A operand with K = N.
+struct PackedGemmArgs {
+  const void* A = nullptr;       // packed_a_bytes(M, K)
+  const void* B = nullptr;       // packed_b_bytes(N, K, epilogue == EPI_SWIGLU)
+  void* C = nullptr;             // EPI_STORE: row-major [M, ldc] bf16; EPI_SWIGLU: packed_a_bytes(M, N)
+  int64_t ldc = 0;
+  int64_t M = 0;
+  int N = 0, K = 0;
+  int epilogue = EPI_STORE;      // EPI_STORE or EPI_SWIGLU
+};
+size_t packed_a_bytes(int64_t rows, int K);
+size_t packed_b_bytes(int N, int K, bool gate_up_pair);
+int launch_pack_a_bf16(const void* X, int64_t ld, int64_t rows, int K, void* dst, hipStream_t s, const char* name);
+// W1 != nullptr: gate/up pair (blocks of 128 rows of W0 followed by the same 128 rows of W1)
+int launch_pack_b_bf16(const void* W0, const void* W1, int N, int K, void* dst, hipStream_t s, const char* name);
+int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* name);
+
 // ---- router -------------------------------------------------------------------
 int launch_router(const void* x, const void* Wgate, int64_t T, int E, int H, moep_dtype dt,
                   float* logits, hipStream_t s);

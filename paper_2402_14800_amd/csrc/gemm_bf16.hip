@@ -32,6 +32,8 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -41,12 +43,6 @@ constexpr int TILE_BYTES = BM * ROW_BYTES;     // one operand tile (BM == BN)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // A tile then B tile
 constexpr int LDS_BYTES = 2 * STAGE_BYTES;     // 131072
 static_assert(BM == GEMM_BM, "grouped tile maps are built for 256-row tiles");
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 
 struct KArgs {
   const u32x4* A; const u32x4* B0; const u32x4* B1;
@@ -127,7 +123,9 @@ void gemm_bf16_kernel(KArgs p) {
       if (r >= row_end) r = row_end - 1;               // tail rows re-read the last valid row
       const int64_t src = p.a_rows ? (int64_t)p.a_rows[r] : r;
       a_off[i] = (uint32_t)src * p.lda_chunks + cch;
-      int n = EPI == EPI_SWIGLU ? tn * 128 + (tr & 127) : tn * BN + tr;
+      // LDS row 32 P + 16 b + f of the B tile holds weight row 32 P + 8 (f >> 2) + 4 b + (f & 3) (see epilogue).
+      const int trp = (tr & ~31) | ((tr & 12) << 1) | ((tr & 16) >> 2) | (tr & 3);
+      int n = EPI == EPI_SWIGLU ? tn * 128 + (trp & 127) : tn * BN + trp;
       if (n >= p.N) n = p.N - 1;
       b_off[i] = (uint32_t)n * p.ldb_chunks + cch;
     }
@@ -189,7 +187,7 @@ void gemm_bf16_kernel(KArgs p) {
 #define MOEP_MFMA(slot)                                                                       \
   _Pragma("unroll") for (int i = 0; i < 8; ++i)                                               \
     _Pragma("unroll") for (int j = 0; j < 4; ++j)                                             \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
 #define MOEP_INTERLEAVE_READS()                                                               \
   _Pragma("unroll") for (int q_ = 0; q_ < 12; ++q_) {                                         \
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                        \
@@ -236,32 +234,52 @@ void gemm_bf16_kernel(KArgs p) {
 #undef MOEP_WAIT_ALL
 
   // ---- epilogue ---------------------------------------------------------------------
-  // Accumulator layout of a 16x16 tile: register v of lane l holds row 4 (l / 16) + v, column l % 16.
-  const int col_in = lane & 15;
-  const int row_in = 4 * (lane >> 4);
+  // The MFMAs were issued with the weight fragment as the first operand, so a 16x16 accumulator tile is
+  // the TRANSPOSE of the output tile: register v of lane l holds output row (l % 16) of row group i and
+  // fragment row f = 4 (l / 16) + v of weight tile j.  The B tile was loaded with its rows permuted inside
+  // every block of 32 (LDS row 32 P + 16 b + f = weight row 32 P + 8 (f / 4) + 4 b + f % 4), hence tiles
+  // 2 P and 2 P + 1 together give each lane 8 CONSECUTIVE output columns 32 P + 8 (l / 16) .. + 7:
+  // one 16-byte store of bf16 (two of fp32) per lane, 64 contiguous bytes per row and store.
+  const int q8 = 8 * (lane >> 4);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
+    const int64_t r = row0 + wm * 128 + i * 16 + (lane & 15);
+    if (r >= row_end) continue;
+    if (EPI == EPI_SWIGLU) {
+      const int n = tn * 128 + wn * 32 + q8;
+      if (n < p.N) {
+        bf16x2 o[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int64_t r = row0 + wm * 128 + i * 16 + row_in + v;
-      if (r >= row_end) continue;
-      if (EPI == EPI_SWIGLU) {
+        for (int c = 0; c < 4; ++c) {
+          f32x2 h;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int n = tn * 128 + wn * 32 + j * 16 + col_in;
-          if (n < p.N) {
-            const float g = acc[i][j][v], u = acc[i][j + 2][v];
-            const float h = g / (1.0f + __expf(-g)) * u;
-            ((uint16_t*)p.C)[r * p.ldc + n] = f32_to_bf16_rne(h);
+          for (int d = 0; d < 2; ++d) {
+            const int b = c >> 1, v = 2 * (c & 1) + d;
+            const float g = acc[i][b][v], u = acc[i][2 + b][v];
+            h[d] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
           }
+          o[c] = __builtin_convertvector(h, bf16x2);
         }
-      } else {
+        *(u32x4*)((uint16_t*)p.C + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
+      }
+    } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int n = tn * BN + wn * 64 + j * 16 + col_in;
-          if (n >= p.N) continue;
-          if (EPI == EPI_STORE) ((uint16_t*)p.C)[r * p.ldc + n] = f32_to_bf16_rne(acc[i][j][v]);
-          else ((float*)p.C)[r * p.ldc + n] = p.row_scale[r] * acc[i][j][v];
+      for (int P = 0; P < 2; ++P) {
+        const int n = tn * BN + wn * 64 + 32 * P + q8;
+        if (n >= p.N) continue;
+        if (EPI == EPI_STORE) {
+          bf16x2 o[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const f32x2 h = {acc[i][2 * P + (c >> 1)][2 * (c & 1)], acc[i][2 * P + (c >> 1)][2 * (c & 1) + 1]};
+            o[c] = __builtin_convertvector(h, bf16x2);
+          }
+          *(u32x4*)((uint16_t*)p.C + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
+        } else {
+          const float sc = p.row_scale[r];
+          float* dst = (float*)p.C + r * p.ldc + n;
+          *(f32x4*)dst = sc * acc[i][2 * P];
+          *(f32x4*)(dst + 4) = sc * acc[i][2 * P + 1];
         }
       }
     }
@@ -287,6 +305,10 @@ int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name) {
   if (g.K % BK || g.K <= 0) return fail(MOEP_EUNSUPPORTED, "%s: K=%d must be a positive multiple of %d", name, g.K, BK);
   if (g.lda % 8 || g.ldc <= 0) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
   if (g.M <= 0 || g.N <= 0) return MOEP_OK;
+  // 16-byte loads and stores: operand bases and row pitches must keep every 8-element group aligned
+  if (((uintptr_t)g.A | (uintptr_t)g.B0 | (uintptr_t)g.B1 | (uintptr_t)g.C) & 15)
+    return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
+  if (g.N % 8 || g.ldc % 8) return fail(MOEP_EUNSUPPORTED, "%s: N=%d and ldc must be multiples of 8", name, g.N);
   KArgs k;
   k.A = (const u32x4*)g.A; k.B0 = (const u32x4*)g.B0; k.B1 = (const u32x4*)g.B1;
   k.a_rows = g.a_rows; k.C = g.C; k.row_scale = g.row_scale;

@@ -1,0 +1,442 @@
+// bf16 GEMM for gfx950 on PACKED operands: C = epilogue(A B^T), fp32 accumulate on the MFMA units
+// (v_mfma_f32_16x16x32_bf16).  Used for the dense expert pass (every expert on every token, Sec. 3.1 /
+// Sec. 3.2), where the operands are re-read many times and re-laying them out once is free.
+//
+// Packed layout.  A matrix X [R, K] is cut into blocks of 256 rows x 32 k-values ("slices").  Block
+// (row tile t, slice s) is 16 KB, stored contiguously at ((t * K/32) + s) * 16 KB; inside it row p
+// takes 64 bytes and its four 16-byte chunks are permuted, chunk c at position c ^ ((p >> 2) & 3).
+// That is exactly the image the kernel wants in LDS (fragment reads of 16 consecutive rows are then
+// free of bank conflicts), so a wavefront's direct global->LDS load moves 1 KB of CONSECUTIVE bytes:
+// eight full cache lines per instruction whatever K is, where the row-major layout offers 128-byte
+// pieces one row pitch apart (or half lines, with 32-wide slices).
+// Weight blocks carry two more permutations (see pack_kernel): the rows of every group of 32 are
+// reordered so that the transposed accumulator tiles give each lane 8 consecutive output columns, and
+// for the gate/up projection a block holds 128 rows of W1 followed by the same 128 rows of W3.
+//
+// Kernel.  One workgroup of 512 threads (8 wavefronts, 2 along M x 4 along N) owns a 256 x 256 tile of
+// the accumulator (256 x 128 outputs in SwiGLU mode); a wavefront owns 128 x 64 = 8 x 4 MFMA tiles.
+// K is walked one slice (one MFMA depth) at a time through a ring of NS = 5 LDS stages of 32 KB.  In
+// the step that multiplies slice g a wavefront also issues its 4 direct loads of slice g + NS (one per
+// 8 MFMAs, into the stage slice g just left) and reads the fragments of slice g + 1 into the other
+// half of a double-buffered fragment register set.  Loads are therefore spread evenly over the step,
+// never issued in bursts, and have NS - 2 whole steps to land: with the row-major two-stage kernel the
+// wavefronts spent a large part of every step blocked in the issue of a burst of loads that the memory
+// pipeline accepts at a fixed rate.
+// Workgroups are persistent (one per compute unit) and the ring runs across tile boundaries: while the
+// last slices of a tile are multiplied and its epilogue runs, the first NS slices of the workgroup's
+// next tile are already being fetched.
+//
+// Epilogues.  The MFMAs take the weight fragment as first operand, so an accumulator tile is the
+// transpose of the output tile and (with the row permutation above) a lane holds 8 consecutive output
+// columns of one row: one 16-byte store.  SwiGLU mode (Sec. 3.1) forms silu(gate) * up in registers,
+// rounds once to bf16 and writes the result in the PACKED layout of an A operand with K = N, ready
+// for the down projection: 16 rows x 64 bytes = 1 KB contiguous per wavefront store.
+//
+// Workgroup order: logical tile ids are dealt round-robin to the 8 XCDs (as the hardware deals
+// workgroups) and remapped so that every XCD works on a contiguous run of tiles, GROUP_M M-tiles deep
+// before moving along N, so that the 32 tiles in flight on one XCD share operand panels in its L2.
+#include "common.h"
+
+namespace moep {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
+
+constexpr int THREADS = 512;
+constexpr int NS = 5;                       // ring stages
+constexpr int SLICE = 256 * 64;             // one operand block: 256 rows x 32 bf16
+constexpr int STAGE = 2 * SLICE;            // A block then B block
+constexpr int LDS_BYTES = NS * STAGE;       // 160 KB
+static_assert(GEMM_BM == 256, "tiles are 256 rows");
+
+// LDS row p of a weight block holds weight row perm32(p) of the tile: inside every group of 32 rows,
+// LDS row 16 b + f is weight row 8 (f >> 2) + 4 b + (f & 3).
+__host__ __device__ constexpr int perm32(int p) {
+  return (p & ~31) | ((p & 12) << 1) | ((p & 16) >> 2) | (p & 3);
+}
+
+// ---- packing ---------------------------------------------------------------------------------
+// mode 0: A operand, block row p of tile t = source row 256 t + p.
+// mode 1: weight, 256 output columns per tile: block row p = row 256 t + perm32(p) of W0.
+// mode 2: gate/up weight pair, 128 output columns per tile: block row p < 128 = row 128 t + perm32(p) of
+//         W0, block row p >= 128 = row 128 t + perm32(p - 128) of W1.
+// Rows beyond the last one re-read the last row (their products are never stored).
+// One workgroup moves a pair of slices (64 k-values) of one tile, so that whole 128-byte lines are read.
+struct PackArgs {
+  const u32x4* W0; const u32x4* W1;
+  u32x4* dst;
+  int64_t ld_chunks;      // source leading dimension in 16-byte chunks
+  int64_t rows;           // valid source rows
+  int nsl;                // K / 32
+  int mode;
+};
+
+__global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
+  const int t = blockIdx.y;
+  const int sp = blockIdx.x;                 // slice pair
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int q = it * 256 + threadIdx.x;    // 2048 chunks: 256 rows x 8 chunks of a 128-byte line
+    const int row = q >> 3, c8 = q & 7;
+    const u32x4* src = p.W0;
+    int64_t r;
+    if (p.mode == 0) r = (int64_t)t * 256 + row;
+    else if (p.mode == 1) r = (int64_t)t * 256 + perm32(row);
+    else {
+      r = (int64_t)t * 128 + perm32(row & 127);
+      if (row >= 128) src = p.W1;
+    }
+    if (r >= p.rows) r = p.rows - 1;
+    const u32x4 v = src[r * p.ld_chunks + (int64_t)sp * 8 + c8];
+    const int s = 2 * sp + (c8 >> 2);
+    const int pos = (c8 & 3) ^ ((row >> 2) & 3);
+    p.dst[((int64_t)t * p.nsl + s) * 1024 + row * 4 + pos] = v;
+  }
+}
+
+// ---- GEMM --------------------------------------------------------------------------------------
+struct KArgs {
+  const char* A;          // packed, tile-major
+  const char* B;          // packed weight blocks
+  void* C;                // EPI_STORE: row-major bf16 [M, ldc]; EPI_SWIGLU: packed A operand with K = N
+  int64_t M, ldc;
+  int N;                  // output columns
+  int nsl;                // K / 32
+  int m_tiles, n_tiles;
+};
+
+template <int EPI>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_packed_kernel(KArgs p) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = wave_u >> 2, wn = wave_u & 3;
+  const int nsl = p.nsl;
+  const uint32_t nblk = (uint32_t)p.m_tiles * (uint32_t)p.n_tiles;
+  const uint32_t G = gridDim.x;
+
+  // Logical tile id -> (tm, tn).  Ids i, i + 8, ... belong to XCD i % 8 (the grid is a multiple of 8 or
+  // a single round); every XCD gets a contiguous run of tiles, GROUP_M M-tiles deep.
+  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;
+  auto decode = [&](uint32_t L, int& tm, int& tn) {
+    const uint32_t per = nblk >> 3, rem = nblk & 7;
+    const uint32_t xcd = L & 7, j = L >> 3;
+    const uint32_t bid = xcd * per + (xcd < rem ? xcd : rem) + j;
+    const uint32_t group_sz = GROUP_M * (uint32_t)p.n_tiles;
+    const uint32_t group = bid / group_sz;
+    const uint32_t first_m = group * GROUP_M;
+    const uint32_t gm = min((uint32_t)p.m_tiles - first_m, GROUP_M);
+    const uint32_t in_group = bid - group * group_sz;
+    tm = (int)(first_m + in_group % gm);
+    tn = (int)(in_group / gm);
+  };
+
+  // ---- loader state (all wave-uniform) ----------------------------------------------------------
+  // A wavefront moves 2 KB of each operand block per slice: KB 2 w and 2 w + 1.
+  uint32_t L_ld = blockIdx.x;
+  if (L_ld >= nblk) return;
+  int tm_ld, tn_ld;
+  decode(L_ld, tm_ld, tn_ld);
+  const char* a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;
+  const char* b_ld = p.B + ((size_t)tn_ld * nsl) * SLICE + wave_u * 2048;
+  int s_ld = 0;
+  int st_ld = 0;                      // byte offset of the stage the next slice goes to
+  bool ld_ok = true;
+  const uint32_t lane_off = lane * 16;
+  typedef __attribute__((address_space(3))) char lds_char;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  lds_char* const lds3 = (lds_char*)lds;
+#define MOEP_LOAD1(q)                                                                           \
+  __builtin_amdgcn_global_load_lds((gptr_t)(((q) < 2 ? a_ld : b_ld) + ((q) & 1) * 1024 + lane_off), \
+      (__attribute__((address_space(3))) void*)(lds3 + st_ld + ((q) < 2 ? 0 : SLICE) + wave_u * 2048 + ((q) & 1) * 1024), 16, 0, 0);
+  // after a slice has been issued: next slice, next stage, possibly next tile of this workgroup
+#define MOEP_ADVANCE_LOADER()                                                                   \
+  {                                                                                             \
+    st_ld = st_ld + STAGE == LDS_BYTES ? 0 : st_ld + STAGE;                                     \
+    if (ld_ok) {                                                                                \
+      a_ld += SLICE; b_ld += SLICE;                                                             \
+      if (++s_ld == nsl) {                                                                      \
+        s_ld = 0;                                                                               \
+        L_ld += G;                                                                              \
+        if (L_ld < nblk) {                                                                      \
+          decode(L_ld, tm_ld, tn_ld);                                                           \
+          a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;                           \
+          b_ld = p.B + ((size_t)tn_ld * nsl) * SLICE + wave_u * 2048;                           \
+        } else {                                                                                \
+          /* past the end of this workgroup's stream: keep re-reading its last slice (in bounds; it  \
+             lands in stages nobody reads again), so that every step issues the same loads and the   \
+             wait counts below hold to the end */                                               \
+          ld_ok = false;                                                                        \
+          a_ld -= SLICE; b_ld -= SLICE;                                                         \
+        }                                                                                       \
+      }                                                                                         \
+    }                                                                                           \
+  }
+
+  // ---- fragment addresses -------------------------------------------------------------------------
+  // MFMA 16x16x32: lane l supplies row (l & 15) and k-values 8 (l >> 4) .. + 7 of both operands, i.e.
+  // chunk (l >> 4) of the row, found at position chunk ^ ((row >> 2) & 3); tile rows are multiples of 16
+  // apart, so the permutation depends on the lane only and every fragment is base + constant.
+  const int frow = lane & 15, fk = lane >> 4;
+  const int fpos = (fk ^ ((frow >> 2) & 3)) << 4;
+  const int a_fb = (wm * 128 + frow) * 64 + fpos;
+  const int b_fb = SLICE + ((EPI == EPI_SWIGLU ? wn * 32 : wn * 64) + frow) * 64 + fpos;
+  int st_rd = 0;                      // byte offset of the stage the next fragment read takes
+
+  f32x4 acc[8][4];
+#define MOEP_ZERO_ACC()                                                                         \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                 \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+      _Pragma("unroll") for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+  MOEP_ZERO_ACC()
+  bf16x8 fa[2][8], fb[2][4];
+  // B tile j of a wavefront: SwiGLU: gate tiles 0, 1 and up tiles 2, 3 (128 rows further) of the same
+  // 32 columns; otherwise four consecutive 16-row tiles.
+#define MOEP_RB(slot, j)                                                                        \
+  fb[slot][j] = *(const bf16x8*)(lds + st_rd + b_fb + (EPI == EPI_SWIGLU ? ((j) >> 1) * 8192 + ((j) & 1) * 1024 : (j) * 1024));
+#define MOEP_RA(slot, i) fa[slot][i] = *(const bf16x8*)(lds + st_rd + a_fb + (i) * 1024);
+#define MOEP_MFMA(slot)                                                                         \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                 \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+  // Source order = wanted issue order (a direct load writes LDS, so the compiler keeps it ordered with
+  // the fragment reads around it): three fragment reads, one direct load, four times over, spread over
+  // the 32 MFMAs by the scheduling groups below.
+#define MOEP_READS_LOADS(slot)                                                                  \
+  MOEP_RB(slot, 0) MOEP_RB(slot, 1) MOEP_RB(slot, 2) MOEP_LOAD1(0)                              \
+  MOEP_RB(slot, 3) MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_LOAD1(1)                              \
+  MOEP_RA(slot, 2) MOEP_RA(slot, 3) MOEP_RA(slot, 4) MOEP_LOAD1(2)                              \
+  MOEP_RA(slot, 5) MOEP_RA(slot, 6) MOEP_RA(slot, 7) MOEP_LOAD1(3)
+#define MOEP_READS(slot)                                                                        \
+  MOEP_RB(slot, 0) MOEP_RB(slot, 1) MOEP_RB(slot, 2) MOEP_RB(slot, 3)                           \
+  MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_RA(slot, 2) MOEP_RA(slot, 3)                           \
+  MOEP_RA(slot, 4) MOEP_RA(slot, 5) MOEP_RA(slot, 6) MOEP_RA(slot, 7)
+#define MOEP_SCHED(LOADS)                                                                       \
+  _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                                            \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                               \
+  }
+  // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, lgkmcnt in bits 11:8 (0 here), expcnt 6:4 left at 7.
+  // Loads complete in issue order, so "at most (NS - 2) * 4 outstanding" means the slice the next step
+  // reads has landed (this step's slice and NS - 2 older ones may still be in flight; stores of an
+  // epilogue only add to the count).
+  constexpr int VM_MAIN = (NS - 2) * 4;
+  constexpr int W_MAIN = 0x0070 | (VM_MAIN & 15) | ((VM_MAIN >> 4) << 14);
+  // One step: multiply the slice whose fragments are in `slot`; meanwhile fetch the slice NS ahead and read
+  // the next slice's fragments into the other slot.  The barrier at the end tells every wavefront that
+  // the next slice has landed for all of them and that all of them have read this step's fragments.
+#define MOEP_STEP(slot)                                                                         \
+  {                                                                                             \
+    MOEP_READS_LOADS((slot) ^ 1)                                                                \
+    MOEP_MFMA(slot)                                                                             \
+    MOEP_SCHED(true)                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                          \
+    __builtin_amdgcn_s_waitcnt(W_MAIN);                                                         \
+    __builtin_amdgcn_s_barrier();                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                          \
+    MOEP_ADVANCE_LOADER()                                                                       \
+    st_rd = st_rd + STAGE == LDS_BYTES ? 0 : st_rd + STAGE;                                     \
+  }
+
+  // ---- prologue: the first NS slices of this workgroup's stream ---------------------------------------
+#pragma unroll 1
+  for (int n = 0; n < NS; ++n) {
+    MOEP_LOAD1(0) MOEP_LOAD1(1) MOEP_LOAD1(2) MOEP_LOAD1(3)
+    MOEP_ADVANCE_LOADER()
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  MOEP_READS(0)
+  st_rd = STAGE;
+  __builtin_amdgcn_sched_barrier(0);
+
+  uint32_t L_mm = blockIdx.x;
+  int tm, tn;
+  decode(L_mm, tm, tn);
+  int s_mm = 0;
+  for (;;) {
+    MOEP_STEP(0)
+    MOEP_STEP(1)
+    s_mm += 2;
+    if (s_mm < nsl) continue;
+
+    // ---- epilogue of tile (tm, tn) ------------------------------------------------------------------
+    // Register v of lane l of accumulator tile (i, j) holds output row 16 i + (l % 16) of the wavefront's
+    // 128 rows and fragment row f = 4 (l / 16) + v of weight tile j; with the row permutation of the weight
+    // blocks, tiles 2 P and 2 P + 1 together give the lane the 8 consecutive columns 32 P + 8 (l / 16) .. + 7.
+    const int q8 = 8 * (lane >> 4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int prow = wm * 128 + i * 16 + (lane & 15);          // row inside the tile
+      const int64_t r = (int64_t)tm * 256 + prow;
+      if (r >= p.M) continue;
+      if (EPI == EPI_SWIGLU) {
+        const int n = tn * 128 + wn * 32 + q8;
+        if (n < p.N) {
+          bf16x2 o[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            f32x2 h;
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+              const int b = c >> 1, v = 2 * (c & 1) + d;
+              const float g = acc[i][b][v], u = acc[i][2 + b][v];
+              h[d] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+            }
+            o[c] = __builtin_convertvector(h, bf16x2);
+          }
+          // packed A operand with K = N: slice n / 32, chunk (l / 16) of row prow
+          char* dst = (char*)p.C + ((size_t)tm * (p.N >> 5) + (n >> 5)) * SLICE + prow * 64 +
+                      (((lane >> 4) ^ ((prow >> 2) & 3)) << 4);
+          *(u32x4*)dst = __builtin_bit_cast(u32x4, o);
+        }
+      } else {
+#pragma unroll
+        for (int P = 0; P < 2; ++P) {
+          const int n = tn * 256 + wn * 64 + 32 * P + q8;
+          if (n >= p.N) continue;
+          bf16x2 o[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const f32x2 h = {acc[i][2 * P + (c >> 1)][2 * (c & 1)], acc[i][2 * P + (c >> 1)][2 * (c & 1) + 1]};
+            o[c] = __builtin_convertvector(h, bf16x2);
+          }
+          *(u32x4*)((uint16_t*)p.C + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
+        }
+      }
+    }
+    L_mm += G;
+    if (L_mm >= nblk) break;   // (the loads still in flight are re-reads; the wavefront ends when they are back)
+    decode(L_mm, tm, tn);
+    s_mm = 0;
+    MOEP_ZERO_ACC()
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);   // the re-reads still in flight target this workgroup's LDS
+#undef MOEP_LOAD1
+#undef MOEP_ADVANCE_LOADER
+#undef MOEP_ZERO_ACC
+#undef MOEP_RB
+#undef MOEP_RA
+#undef MOEP_MFMA
+#undef MOEP_READS_LOADS
+#undef MOEP_READS
+#undef MOEP_SCHED
+#undef MOEP_STEP
+}
+
+int compute_units() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      return 256;
+    n = v;
+  }
+  return n;
+}
+
+template <int EPI>
+int launch(const KArgs& k, hipStream_t s) {
+  static bool attr_set = false;   // raising the dynamic LDS limit is per function, once
+  if (!attr_set) {
+    MOEP_HIP(hipFuncSetAttribute((const void*)gemm_packed_kernel<EPI>,
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    attr_set = true;
+  }
+  const int64_t nblk = (int64_t)k.m_tiles * k.n_tiles;
+  int grid = compute_units() & ~7;            // one persistent workgroup per compute unit, a multiple of 8
+  if (grid < 8) grid = 8;
+  if (nblk < grid) grid = (int)nblk;          // a single round: any size
+  hipLaunchKernelGGL(gemm_packed_kernel<EPI>, dim3(grid), dim3(THREADS), LDS_BYTES, s, k);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+}  // namespace
+
+size_t packed_a_bytes(int64_t rows, int K) {
+  return (size_t)ceil_div(rows, 256) * 256 * (size_t)K * 2;
+}
+
+size_t packed_b_bytes(int N, int K, bool gate_up_pair) {
+  return (size_t)ceil_div(N, gate_up_pair ? 128 : 256) * 256 * (size_t)K * 2;
+}
+
+static int launch_pack(const void* W0, const void* W1, int64_t ld, int64_t rows, int K, int mode, void* dst,
+                       hipStream_t s, const char* name) {
+  if (K <= 0 || K % 64 || ld % 8) return fail(MOEP_EUNSUPPORTED, "%s: K=%d must be a positive multiple of 64", name, K);
+  if (rows <= 0) return MOEP_OK;
+  if (((uintptr_t)W0 | (uintptr_t)W1 | (uintptr_t)dst) & 15) return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
+  const int64_t tiles = ceil_div(rows, mode == 2 ? 128 : 256);
+  if (tiles > 65535) {
+    // grid.y is 16 bits wide: pack in runs of tiles
+    const int64_t run = 32768;
+    for (int64_t t0 = 0; t0 < tiles; t0 += run) {
+      const int64_t nt = tiles - t0 < run ? tiles - t0 : run;
+      const int64_t r0 = t0 * (mode == 2 ? 128 : 256);
+      PackArgs p;
+      p.W0 = (const u32x4*)((const char*)W0 + r0 * ld * 2);
+      p.W1 = W1 ? (const u32x4*)((const char*)W1 + r0 * ld * 2) : nullptr;
+      p.dst = (u32x4*)((char*)dst + (size_t)t0 * (K / 32) * SLICE);
+      p.ld_chunks = ld / 8; p.rows = rows - r0; p.nsl = K / 32; p.mode = mode;
+      Timed t(name, s);
+      hipLaunchKernelGGL(pack_kernel, dim3(K / 64, (unsigned)nt), dim3(256), 0, s, p);
+      MOEP_HIP(hipGetLastError());
+    }
+    return MOEP_OK;
+  }
+  PackArgs p;
+  p.W0 = (const u32x4*)W0; p.W1 = (const u32x4*)W1; p.dst = (u32x4*)dst;
+  p.ld_chunks = ld / 8; p.rows = rows; p.nsl = K / 32; p.mode = mode;
+  Timed t(name, s);
+  hipLaunchKernelGGL(pack_kernel, dim3(K / 64, (unsigned)tiles), dim3(256), 0, s, p);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+int launch_pack_a_bf16(const void* X, int64_t ld, int64_t rows, int K, void* dst, hipStream_t s, const char* name) {
+  return launch_pack(X, nullptr, ld, rows, K, 0, dst, s, name);
+}
+
+int launch_pack_b_bf16(const void* W0, const void* W1, int N, int K, void* dst, hipStream_t s, const char* name) {
+  return launch_pack(W0, W1, K, N, K, W1 ? 2 : 1, dst, s, name);
+}
+
+int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* name) {
+  if (g.K <= 0 || g.K % 64) return fail(MOEP_EUNSUPPORTED, "%s: K=%d must be a positive multiple of 64", name, g.K);
+  if (g.N <= 0 || g.N % 32) return fail(MOEP_EUNSUPPORTED, "%s: N=%d must be a positive multiple of 32", name, g.N);
+  if (g.M <= 0) return MOEP_OK;
+  if (((uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C) & 15)
+    return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
+  if (g.epilogue == EPI_STORE && (g.ldc % 8 || g.ldc < g.N)) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
+  KArgs k;
+  k.A = (const char*)g.A; k.B = (const char*)g.B; k.C = g.C;
+  k.M = g.M; k.ldc = g.ldc; k.N = g.N; k.nsl = g.K / 32;
+  const int64_t m_tiles = ceil_div(g.M, 256);
+  const int64_t n_tiles = ceil_div(g.N, g.epilogue == EPI_SWIGLU ? 128 : 256);
+  if (m_tiles * n_tiles >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "%s: too many tiles", name);
+  k.m_tiles = (int)m_tiles; k.n_tiles = (int)n_tiles;
+  Timed t(name, s);
+  switch (g.epilogue) {
+    case EPI_STORE: return launch<EPI_STORE>(k, s);
+    case EPI_SWIGLU: return launch<EPI_SWIGLU>(k, s);
+  }
+  return fail(MOEP_EINVAL, "%s: unsupported epilogue %d", name, g.epilogue);
+}
+
+}  // namespace moep

@@ -59,7 +59,12 @@ def test_subset_helpers_reject_bad_arguments():
 
 def test_workspace_queries_are_pure_host_arithmetic():
     assert binding.moe_expert_outputs_workspace(512, 4, 64, 128, binding.MOEP_F32) == 512 * 128 * 4
-    assert binding.moe_expert_outputs_workspace(16384, 8, 1024, 3584, binding.MOEP_BF16) == 16384 * 3584 * 2
+    # bf16: h and x in the packed operand layout (rows padded to 256) plus one expert's packed W1/W3 pair and W2
+    T, H, F = 16384, 1024, 3584
+    assert binding.moe_expert_outputs_workspace(T, 8, H, F, binding.MOEP_BF16) == (
+        T * F * 2 + T * H * 2 + (F // 128) * 256 * H * 2 + (H // 256) * 256 * F * 2)
+    assert binding.moe_expert_outputs_workspace(300, 8, 64, 192, binding.MOEP_BF16) == (
+        512 * 192 * 2 + 512 * 64 * 2 + 2 * 256 * 64 * 2 + 1 * 256 * 192 * 2)
     w6 = binding.prune_enumerate_workspace(16384, 8, 1024, 2, 6, binding.MOEP_BF16)
     w4 = binding.prune_enumerate_workspace(16384, 8, 1024, 2, 4, binding.MOEP_BF16)
     assert w6 >= 16384 * 64 * 4 and w4 > w6
