@@ -221,8 +221,8 @@ int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const v
     if (int st = launch_pack_a_bf16(x, H, T, H, xp, s, "pack_x")) return st;
     for (int e = 0; e < E; ++e) {
       if (int st = launch_pack_b_bf16((const char*)W1 + (size_t)e * F * H * es, (const char*)W3 + (size_t)e * F * H * es,
-                                      F, H, wgu, s, "pack_w")) return st;
-      if (int st = launch_pack_b_bf16((const char*)W2 + (size_t)e * H * F * es, nullptr, H, F, wdn, s, "pack_w")) return st;
+                                      F, H, 1, wgu, s, "pack_w")) return st;
+      if (int st = launch_pack_b_bf16((const char*)W2 + (size_t)e * H * F * es, nullptr, H, F, 1, wdn, s, "pack_w")) return st;
       PackedGemmArgs up;                          // h = silu(x W1[e]^T) * (x W3[e]^T)
       up.A = xp; up.B = wgu; up.C = hp;
       up.M = T; up.N = F; up.K = H; up.epilogue = EPI_SWIGLU;
@@ -286,6 +286,32 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
 static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, const void* W3,
                           const void* W2, moep_dtype dt, char* w, hipStream_t s, void* plain_out = nullptr) {
   const int H = p.H, F = p.F;
+  if (dt == MOEP_BF16) {
+    // Packed-operand path: the routed rows of x are gathered into one 256-row block per tile, every
+    // expert's weights are re-laid out, and h stays in the packed layout between the two projections.
+    const int32_t* slot_token = (const int32_t*)(w + p.off_slot_token);
+    const int32_t* tile_expert = (const int32_t*)(w + p.off_tile_expert);
+    const int32_t* tile_row0 = (const int32_t*)(w + p.off_tile_row0);
+    const int32_t* seg_end = (const int32_t*)(w + p.off_seg_end);
+    const int32_t* tiles_in_use = tile_expert + p.max_tiles;
+    if (int st = launch_pack_a_gathered_bf16(x, H, slot_token, tile_expert, tile_row0, seg_end, tiles_in_use,
+                                             p.max_tiles, H, w + p.off_xp, s, "pack_x_routed")) return st;
+    if (int st = launch_pack_b_bf16(W1, W3, F, H, p.E, w + p.off_w13, s, "pack_w")) return st;
+    if (int st = launch_pack_b_bf16(W2, nullptr, H, F, p.E, w + p.off_w2, s, "pack_w")) return st;
+    PackedGemmArgs up;
+    up.A = w + p.off_xp; up.B = w + p.off_w13; up.C = w + p.off_h;
+    up.M = p.max_slots; up.N = F; up.K = H; up.epilogue = EPI_SWIGLU;
+    up.tile_expert = tile_expert; up.tile_row0 = tile_row0; up.seg_end = seg_end; up.tiles_in_use = tiles_in_use;
+    up.max_m_tiles = p.max_tiles;
+    if (int st = launch_gemm_bf16_packed(up, s, "gemm_gate_up_swiglu_routed")) return st;
+    PackedGemmArgs down = up;
+    down.A = w + p.off_h; down.B = w + p.off_w2;
+    down.C = plain_out ? plain_out : w + p.off_slot_out; down.ldc = H;
+    down.N = H; down.K = F;
+    down.epilogue = plain_out ? EPI_STORE : EPI_ROWSCALE_F32;
+    down.row_scale = plain_out ? nullptr : (const float*)(w + p.off_slot_scale);
+    return launch_gemm_bf16_packed(down, s, "gemm_down_routed");
+  }
   GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
   up.A = x; up.lda = H; up.a_rows = (const int32_t*)(w + p.off_slot_token);
   up.B0 = W1; up.B1 = W3; up.b_expert_stride = (int64_t)F * H;

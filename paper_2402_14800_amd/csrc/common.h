@@ -73,19 +73,32 @@ int launch_gemm_f32(const GemmArgs& g, hipStream_t s, const char* name);
 // Operands are re-laid out once into 16 KB blocks of 256 rows x 32 k-values (the layout is described in
 // gemm_bf16_packed.hip); EPI_SWIGLU writes its result as a packed A operand with K = N.
 struct PackedGemmArgs {
-  const void* A = nullptr;       // packed_a_bytes(M, K)
-  const void* B = nullptr;       // packed_b_bytes(N, K, epilogue == EPI_SWIGLU)
-  void* C = nullptr;             // EPI_STORE: row-major [M, ldc] bf16; EPI_SWIGLU: packed_a_bytes(M, N)
+  const void* A = nullptr;       // packed A operand, indexed by M tile
+  const void* B = nullptr;       // packed_b_bytes(N, K, epilogue == EPI_SWIGLU) per expert
+  void* C = nullptr;             // EPI_STORE / EPI_ROWSCALE_F32: row-major [rows, ldc]; EPI_SWIGLU: packed A operand, K = N
   int64_t ldc = 0;
-  int64_t M = 0;
+  int64_t M = 0;                 // rows (dense mode)
   int N = 0, K = 0;
-  int epilogue = EPI_STORE;      // EPI_STORE or EPI_SWIGLU
+  int epilogue = EPI_STORE;
+  const float* row_scale = nullptr;
+  // Grouped mode: the same tile map as GemmArgs; A (and a packed C) hold one 256-row block per TILE.
+  const int32_t* tile_expert = nullptr;
+  const int32_t* tile_row0 = nullptr;
+  const int32_t* seg_end = nullptr;
+  const int32_t* tiles_in_use = nullptr;
+  int64_t max_m_tiles = 0;
 };
 size_t packed_a_bytes(int64_t rows, int K);
 size_t packed_b_bytes(int N, int K, bool gate_up_pair);
 int launch_pack_a_bf16(const void* X, int64_t ld, int64_t rows, int K, void* dst, hipStream_t s, const char* name);
-// W1 != nullptr: gate/up pair (blocks of 128 rows of W0 followed by the same 128 rows of W1)
-int launch_pack_b_bf16(const void* W0, const void* W1, int N, int K, void* dst, hipStream_t s, const char* name);
+// grouped: block row p of tile t = row rows_of[tile_row0[t] + p] of X
+int launch_pack_a_gathered_bf16(const void* X, int64_t ld, const int32_t* rows_of, const int32_t* tile_expert,
+                                const int32_t* tile_row0, const int32_t* seg_end, const int32_t* tiles_in_use,
+                                int64_t max_tiles, int K, void* dst, hipStream_t s, const char* name);
+// W1 != nullptr: gate/up pair (blocks of 128 rows of W0 followed by the same 128 rows of W1); `experts`
+// consecutive [N, K] matrices are packed into consecutive packed_b_bytes blocks
+int launch_pack_b_bf16(const void* W0, const void* W1, int N, int K, int experts, void* dst, hipStream_t s,
+                       const char* name);
 int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* name);
 
 // ---- router -------------------------------------------------------------------
@@ -123,7 +136,7 @@ struct SkipPlan {
   int64_t max_slots;     // ks T
   int64_t max_tiles;     // upper bound on M tiles over all experts
   size_t off_logits, off_slot_token, off_slot_scale, off_pos, off_counts, off_seg_end,
-         off_tile_expert, off_tile_row0, off_h, off_slot_out, total;
+         off_tile_expert, off_tile_row0, off_h, off_xp, off_w13, off_w2, off_slot_out, total;
 };
 int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p, bool with_slot_out = true);
 int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,

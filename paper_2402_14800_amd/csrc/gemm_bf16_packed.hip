@@ -47,7 +47,16 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
 constexpr int THREADS = 512;
-constexpr int NS = 5;                       // ring stages
+#ifndef PK_NS
+#define PK_NS 5
+#endif
+#ifndef PK_GM_GU
+#define PK_GM_GU 8
+#endif
+#ifndef PK_GM_DN
+#define PK_GM_DN 4
+#endif
+constexpr int NS = PK_NS;                   // ring stages
 constexpr int SLICE = 256 * 64;             // one operand block: 256 rows x 32 bf16
 constexpr int STAGE = 2 * SLICE;            // A block then B block
 constexpr int LDS_BYTES = NS * STAGE;       // 160 KB
@@ -64,37 +73,58 @@ __host__ __device__ constexpr int perm32(int p) {
 // mode 1: weight, 256 output columns per tile: block row p = row 256 t + perm32(p) of W0.
 // mode 2: gate/up weight pair, 128 output columns per tile: block row p < 128 = row 128 t + perm32(p) of
 //         W0, block row p >= 128 = row 128 t + perm32(p - 128) of W1.
+// mode 3: gathered A operand of a grouped GEMM: block row p of tile t = source row rows_of[tile_row0[t] + p]
+//         (the rows routed to the tile's expert, Sec. 3.3); tiles beyond the number in use are left alone.
 // Rows beyond the last one re-read the last row (their products are never stored).
-// One workgroup moves a pair of slices (64 k-values) of one tile, so that whole 128-byte lines are read.
+// One workgroup moves a pair of slices (64 k-values) of one tile, so that whole 128-byte lines are read;
+// blockIdx.z selects the expert of a weight stack.
 struct PackArgs {
   const u32x4* W0; const u32x4* W1;
   u32x4* dst;
   int64_t ld_chunks;      // source leading dimension in 16-byte chunks
-  int64_t rows;           // valid source rows
+  int64_t rows;           // valid source rows (modes 0..2)
+  int64_t src_expert_chunks, dst_expert_chunks;   // per-expert strides (blockIdx.z)
+  const int32_t* rows_of; const int32_t* tile_expert; const int32_t* tile_row0; const int32_t* seg_end;
+  const int32_t* tiles_in_use;
   int nsl;                // K / 32
   int mode;
 };
 
 __global__ __launch_bounds__(256) void pack_kernel(PackArgs p) {
-  const int t = blockIdx.y;
-  const int sp = blockIdx.x;                 // slice pair
+  const int t = blockIdx.x;
+  const int sp = blockIdx.y;                 // slice pair
+  const u32x4* W0 = p.W0 + (int64_t)blockIdx.z * p.src_expert_chunks;
+  const u32x4* W1 = p.W1 + (int64_t)blockIdx.z * p.src_expert_chunks;
+  u32x4* dst = p.dst + (int64_t)blockIdx.z * p.dst_expert_chunks;
+  int64_t g_row0 = 0, g_end = 0;
+  if (p.mode == 3) {
+    if (t >= *p.tiles_in_use) return;
+    g_row0 = p.tile_row0[t];
+    g_end = p.seg_end[p.tile_expert[t]];
+  }
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int q = it * 256 + threadIdx.x;    // 2048 chunks: 256 rows x 8 chunks of a 128-byte line
     const int row = q >> 3, c8 = q & 7;
-    const u32x4* src = p.W0;
+    const u32x4* src = W0;
     int64_t r;
-    if (p.mode == 0) r = (int64_t)t * 256 + row;
-    else if (p.mode == 1) r = (int64_t)t * 256 + perm32(row);
-    else {
-      r = (int64_t)t * 128 + perm32(row & 127);
-      if (row >= 128) src = p.W1;
+    if (p.mode == 3) {
+      int64_t slot = g_row0 + row;
+      if (slot >= g_end) slot = g_end - 1;
+      r = p.rows_of[slot];
+    } else {
+      if (p.mode == 0) r = (int64_t)t * 256 + row;
+      else if (p.mode == 1) r = (int64_t)t * 256 + perm32(row);
+      else {
+        r = (int64_t)t * 128 + perm32(row & 127);
+        if (row >= 128) src = W1;
+      }
+      if (r >= p.rows) r = p.rows - 1;
     }
-    if (r >= p.rows) r = p.rows - 1;
     const u32x4 v = src[r * p.ld_chunks + (int64_t)sp * 8 + c8];
     const int s = 2 * sp + (c8 >> 2);
     const int pos = (c8 & 3) ^ ((row >> 2) & 3);
-    p.dst[((int64_t)t * p.nsl + s) * 1024 + row * 4 + pos] = v;
+    dst[((int64_t)t * p.nsl + s) * 1024 + row * 4 + pos] = v;
   }
 }
 
@@ -107,9 +137,14 @@ struct KArgs {
   int N;                  // output columns
   int nsl;                // K / 32
   int m_tiles, n_tiles;
+  // grouped mode (rows partitioned into per-expert segments, tile t = rows tile_row0[t] .. of expert
+  // tile_expert[t]; A and a packed C are indexed by TILE, a row-major C by row)
+  const int32_t* tile_expert; const int32_t* tile_row0; const int32_t* seg_end; const int32_t* tiles_in_use;
+  int64_t b_expert_bytes;
+  const float* row_scale;
 };
 
-template <int EPI>
+template <int EPI, bool GROUPED>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gemm_packed_kernel(KArgs p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -119,12 +154,20 @@ void gemm_packed_kernel(KArgs p) {
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int wm = wave_u >> 2, wn = wave_u & 3;
   const int nsl = p.nsl;
-  const uint32_t nblk = (uint32_t)p.m_tiles * (uint32_t)p.n_tiles;
+  // Grouped launches are sized for the largest possible tile map; only its leading entries hold work.
+  const uint32_t m_tiles = GROUPED ? (uint32_t)*p.tiles_in_use : (uint32_t)p.m_tiles;
+  const uint32_t nblk = m_tiles * (uint32_t)p.n_tiles;
   const uint32_t G = gridDim.x;
 
   // Logical tile id -> (tm, tn).  Ids i, i + 8, ... belong to XCD i % 8 (the grid is a multiple of 8 or
   // a single round); every XCD gets a contiguous run of tiles, GROUP_M M-tiles deep.
-  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;
+  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? PK_GM_GU : PK_GM_DN;
+  // weight blocks of the tile's expert
+  auto b_tile = [&](int tm_, int tn_) {
+    const char* b = p.B + ((size_t)tn_ * nsl) * SLICE + wave_u * 2048;
+    if (GROUPED) b += (int64_t)p.tile_expert[tm_] * p.b_expert_bytes;
+    return b;
+  };
   auto decode = [&](uint32_t L, int& tm, int& tn) {
     const uint32_t per = nblk >> 3, rem = nblk & 7;
     const uint32_t xcd = L & 7, j = L >> 3;
@@ -132,7 +175,7 @@ void gemm_packed_kernel(KArgs p) {
     const uint32_t group_sz = GROUP_M * (uint32_t)p.n_tiles;
     const uint32_t group = bid / group_sz;
     const uint32_t first_m = group * GROUP_M;
-    const uint32_t gm = min((uint32_t)p.m_tiles - first_m, GROUP_M);
+    const uint32_t gm = min(m_tiles - first_m, GROUP_M);
     const uint32_t in_group = bid - group * group_sz;
     tm = (int)(first_m + in_group % gm);
     tn = (int)(in_group / gm);
@@ -145,7 +188,7 @@ void gemm_packed_kernel(KArgs p) {
   int tm_ld, tn_ld;
   decode(L_ld, tm_ld, tn_ld);
   const char* a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;
-  const char* b_ld = p.B + ((size_t)tn_ld * nsl) * SLICE + wave_u * 2048;
+  const char* b_ld = b_tile(tm_ld, tn_ld);
   int s_ld = 0;
   int st_ld = 0;                      // byte offset of the stage the next slice goes to
   bool ld_ok = true;
@@ -153,31 +196,39 @@ void gemm_packed_kernel(KArgs p) {
   typedef __attribute__((address_space(3))) char lds_char;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   lds_char* const lds3 = (lds_char*)lds;
+  // per-lane global addresses of this wavefront's part of the next slice (kept in registers so that the
+  // step that issues the loads has no address arithmetic to do first)
+  const char* ga = a_ld + lane_off;
+  const char* gb = b_ld + lane_off;
 #define MOEP_LOAD1(q)                                                                           \
-  __builtin_amdgcn_global_load_lds((gptr_t)(((q) < 2 ? a_ld : b_ld) + ((q) & 1) * 1024 + lane_off), \
+  __builtin_amdgcn_global_load_lds((gptr_t)(((q) < 2 ? ga : gb) + ((q) & 1) * 1024),            \
       (__attribute__((address_space(3))) void*)(lds3 + st_ld + ((q) < 2 ? 0 : SLICE) + wave_u * 2048 + ((q) & 1) * 1024), 16, 0, 0);
-  // after a slice has been issued: next slice, next stage, possibly next tile of this workgroup
+  // After a slice has been issued: next slice, next stage (branch-free, so that it can be scheduled into
+  // the shadow of the MFMAs).  Past the end of the workgroup's stream the loader stays on its last slice:
+  // the re-reads are in bounds and land in stages nobody reads again, every step issues the same loads and
+  // the wait counts below hold to the end.
 #define MOEP_ADVANCE_LOADER()                                                                   \
   {                                                                                             \
+    const int adv_ = ld_ok ? SLICE : 0;                                                         \
+    a_ld += adv_; b_ld += adv_;                                                                 \
+    s_ld += ld_ok ? 1 : 0;                                                                      \
     st_ld = st_ld + STAGE == LDS_BYTES ? 0 : st_ld + STAGE;                                     \
-    if (ld_ok) {                                                                                \
-      a_ld += SLICE; b_ld += SLICE;                                                             \
-      if (++s_ld == nsl) {                                                                      \
-        s_ld = 0;                                                                               \
-        L_ld += G;                                                                              \
-        if (L_ld < nblk) {                                                                      \
-          decode(L_ld, tm_ld, tn_ld);                                                           \
-          a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;                           \
-          b_ld = p.B + ((size_t)tn_ld * nsl) * SLICE + wave_u * 2048;                           \
-        } else {                                                                                \
-          /* past the end of this workgroup's stream: keep re-reading its last slice (in bounds; it  \
-             lands in stages nobody reads again), so that every step issues the same loads and the   \
-             wait counts below hold to the end */                                               \
-          ld_ok = false;                                                                        \
-          a_ld -= SLICE; b_ld -= SLICE;                                                         \
-        }                                                                                       \
-      }                                                                                         \
+    ga = a_ld + lane_off; gb = b_ld + lane_off;                                                 \
+  }
+  // ... and, rarely, the next tile of this workgroup
+#define MOEP_NEXT_LOAD_TILE()                                                                   \
+  if (__builtin_expect(s_ld == nsl, 0)) {                                                       \
+    s_ld = 0;                                                                                   \
+    L_ld += G;                                                                                  \
+    if (L_ld < nblk) {                                                                          \
+      decode(L_ld, tm_ld, tn_ld);                                                               \
+      a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;                               \
+      b_ld = b_tile(tm_ld, tn_ld);                                                              \
+    } else {                                                                                    \
+      ld_ok = false;                                                                            \
+      a_ld -= SLICE; b_ld -= SLICE;                                                             \
     }                                                                                           \
+    ga = a_ld + lane_off; gb = b_ld + lane_off;                                                 \
   }
 
   // ---- fragment addresses -------------------------------------------------------------------------
@@ -189,6 +240,7 @@ void gemm_packed_kernel(KArgs p) {
   const int a_fb = (wm * 128 + frow) * 64 + fpos;
   const int b_fb = SLICE + ((EPI == EPI_SWIGLU ? wn * 32 : wn * 64) + frow) * 64 + fpos;
   int st_rd = 0;                      // byte offset of the stage the next fragment read takes
+  int ra = a_fb, rb = b_fb;           // the same, added to the lane's fragment offsets
 
   f32x4 acc[8][4];
 #define MOEP_ZERO_ACC()                                                                         \
@@ -200,8 +252,8 @@ void gemm_packed_kernel(KArgs p) {
   // B tile j of a wavefront: SwiGLU: gate tiles 0, 1 and up tiles 2, 3 (128 rows further) of the same
   // 32 columns; otherwise four consecutive 16-row tiles.
 #define MOEP_RB(slot, j)                                                                        \
-  fb[slot][j] = *(const bf16x8*)(lds + st_rd + b_fb + (EPI == EPI_SWIGLU ? ((j) >> 1) * 8192 + ((j) & 1) * 1024 : (j) * 1024));
-#define MOEP_RA(slot, i) fa[slot][i] = *(const bf16x8*)(lds + st_rd + a_fb + (i) * 1024);
+  fb[slot][j] = *(const bf16x8*)(lds + rb + (EPI == EPI_SWIGLU ? ((j) >> 1) * 8192 + ((j) & 1) * 1024 : (j) * 1024));
+#define MOEP_RA(slot, i) fa[slot][i] = *(const bf16x8*)(lds + ra + (i) * 1024);
 #define MOEP_MFMA(slot)                                                                         \
   _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                 \
     _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
@@ -218,15 +270,17 @@ void gemm_packed_kernel(KArgs p) {
   MOEP_RB(slot, 0) MOEP_RB(slot, 1) MOEP_RB(slot, 2) MOEP_RB(slot, 3)                           \
   MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_RA(slot, 2) MOEP_RA(slot, 3)                           \
   MOEP_RA(slot, 4) MOEP_RA(slot, 5) MOEP_RA(slot, 6) MOEP_RA(slot, 7)
+  // The down projection reads its fragments early (one read per MFMA, done after 12 of the 32 MFMAs); the
+  // SwiGLU kernel, whose registers are tighter, spreads them over 24 MFMAs (the early form spills there).
 #define MOEP_SCHED(LOADS)                                                                       \
   _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                                            \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
     if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                               \
   }
   // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, lgkmcnt in bits 11:8 (0 here), expcnt 6:4 left at 7.
@@ -243,12 +297,14 @@ void gemm_packed_kernel(KArgs p) {
     MOEP_READS_LOADS((slot) ^ 1)                                                                \
     MOEP_MFMA(slot)                                                                             \
     MOEP_SCHED(true)                                                                            \
+    MOEP_ADVANCE_LOADER()                                                                       \
+    st_rd = st_rd + STAGE == LDS_BYTES ? 0 : st_rd + STAGE;                                     \
+    ra = a_fb + st_rd; rb = b_fb + st_rd;                                                       \
     __builtin_amdgcn_sched_barrier(0);                                                          \
     __builtin_amdgcn_s_waitcnt(W_MAIN);                                                         \
     __builtin_amdgcn_s_barrier();                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                          \
-    MOEP_ADVANCE_LOADER()                                                                       \
-    st_rd = st_rd + STAGE == LDS_BYTES ? 0 : st_rd + STAGE;                                     \
+    MOEP_NEXT_LOAD_TILE()                                                                       \
   }
 
   // ---- prologue: the first NS slices of this workgroup's stream ---------------------------------------
@@ -256,12 +312,14 @@ void gemm_packed_kernel(KArgs p) {
   for (int n = 0; n < NS; ++n) {
     MOEP_LOAD1(0) MOEP_LOAD1(1) MOEP_LOAD1(2) MOEP_LOAD1(3)
     MOEP_ADVANCE_LOADER()
+    MOEP_NEXT_LOAD_TILE()
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_sched_barrier(0);
   MOEP_READS(0)
   st_rd = STAGE;
+  ra = a_fb + st_rd; rb = b_fb + st_rd;
   __builtin_amdgcn_sched_barrier(0);
 
   uint32_t L_mm = blockIdx.x;
@@ -272,18 +330,23 @@ void gemm_packed_kernel(KArgs p) {
     MOEP_STEP(0)
     MOEP_STEP(1)
     s_mm += 2;
-    if (s_mm < nsl) continue;
+    if (__builtin_expect(s_mm < nsl, 1)) continue;
 
     // ---- epilogue of tile (tm, tn) ------------------------------------------------------------------
     // Register v of lane l of accumulator tile (i, j) holds output row 16 i + (l % 16) of the wavefront's
     // 128 rows and fragment row f = 4 (l / 16) + v of weight tile j; with the row permutation of the weight
     // blocks, tiles 2 P and 2 P + 1 together give the lane the 8 consecutive columns 32 P + 8 (l / 16) .. + 7.
     const int q8 = 8 * (lane >> 4);
+    int64_t row0 = (int64_t)tm * 256, row_end = p.M;
+    if (GROUPED) {
+      row0 = p.tile_row0[tm];
+      row_end = p.seg_end[p.tile_expert[tm]];
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int prow = wm * 128 + i * 16 + (lane & 15);          // row inside the tile
-      const int64_t r = (int64_t)tm * 256 + prow;
-      if (r >= p.M) continue;
+      const int64_t r = row0 + prow;
+      if (r >= row_end) continue;
       if (EPI == EPI_SWIGLU) {
         const int n = tn * 128 + wn * 32 + q8;
         if (n < p.N) {
@@ -309,13 +372,20 @@ void gemm_packed_kernel(KArgs p) {
         for (int P = 0; P < 2; ++P) {
           const int n = tn * 256 + wn * 64 + 32 * P + q8;
           if (n >= p.N) continue;
-          bf16x2 o[4];
+          if (EPI == EPI_STORE) {
+            bf16x2 o[4];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const f32x2 h = {acc[i][2 * P + (c >> 1)][2 * (c & 1)], acc[i][2 * P + (c >> 1)][2 * (c & 1) + 1]};
-            o[c] = __builtin_convertvector(h, bf16x2);
+            for (int c = 0; c < 4; ++c) {
+              const f32x2 h = {acc[i][2 * P + (c >> 1)][2 * (c & 1)], acc[i][2 * P + (c >> 1)][2 * (c & 1) + 1]};
+              o[c] = __builtin_convertvector(h, bf16x2);
+            }
+            *(u32x4*)((uint16_t*)p.C + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
+          } else {                                               // EPI_ROWSCALE_F32
+            const float sc = p.row_scale[r];
+            float* dst = (float*)p.C + r * p.ldc + n;
+            *(f32x4*)dst = sc * acc[i][2 * P];
+            *(f32x4*)(dst + 4) = sc * acc[i][2 * P + 1];
           }
-          *(u32x4*)((uint16_t*)p.C + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
         }
       }
     }
@@ -328,6 +398,7 @@ void gemm_packed_kernel(KArgs p) {
   __builtin_amdgcn_s_waitcnt(0x0070);   // the re-reads still in flight target this workgroup's LDS
 #undef MOEP_LOAD1
 #undef MOEP_ADVANCE_LOADER
+#undef MOEP_NEXT_LOAD_TILE
 #undef MOEP_ZERO_ACC
 #undef MOEP_RB
 #undef MOEP_RA
@@ -350,11 +421,11 @@ int compute_units() {
   return n;
 }
 
-template <int EPI>
+template <int EPI, bool GROUPED>
 int launch(const KArgs& k, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic LDS limit is per function, once
   if (!attr_set) {
-    MOEP_HIP(hipFuncSetAttribute((const void*)gemm_packed_kernel<EPI>,
+    MOEP_HIP(hipFuncSetAttribute((const void*)gemm_packed_kernel<EPI, GROUPED>,
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
     attr_set = true;
   }
@@ -362,7 +433,20 @@ int launch(const KArgs& k, hipStream_t s) {
   int grid = compute_units() & ~7;            // one persistent workgroup per compute unit, a multiple of 8
   if (grid < 8) grid = 8;
   if (nblk < grid) grid = (int)nblk;          // a single round: any size
-  hipLaunchKernelGGL(gemm_packed_kernel<EPI>, dim3(grid), dim3(THREADS), LDS_BYTES, s, k);
+  hipLaunchKernelGGL((gemm_packed_kernel<EPI, GROUPED>), dim3(grid), dim3(THREADS), LDS_BYTES, s, k);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+int launch_pack(PackArgs p, int64_t tiles, int K, int experts, hipStream_t s, const char* name) {
+  if (K <= 0 || K % 64) return fail(MOEP_EUNSUPPORTED, "%s: K=%d must be a positive multiple of 64", name, K);
+  if (tiles <= 0 || experts <= 0) return MOEP_OK;
+  if (((uintptr_t)p.W0 | (uintptr_t)p.W1 | (uintptr_t)p.dst) & 15)
+    return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
+  if (tiles >= ((int64_t)1 << 31) || K / 64 > 65535 || experts > 65535) return fail(MOEP_EUNSUPPORTED, "%s: too large", name);
+  p.nsl = K / 32;
+  Timed t(name, s);
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)tiles, K / 64, experts), dim3(256), 0, s, p);
   MOEP_HIP(hipGetLastError());
   return MOEP_OK;
 }
@@ -377,44 +461,32 @@ size_t packed_b_bytes(int N, int K, bool gate_up_pair) {
   return (size_t)ceil_div(N, gate_up_pair ? 128 : 256) * 256 * (size_t)K * 2;
 }
 
-static int launch_pack(const void* W0, const void* W1, int64_t ld, int64_t rows, int K, int mode, void* dst,
-                       hipStream_t s, const char* name) {
-  if (K <= 0 || K % 64 || ld % 8) return fail(MOEP_EUNSUPPORTED, "%s: K=%d must be a positive multiple of 64", name, K);
-  if (rows <= 0) return MOEP_OK;
-  if (((uintptr_t)W0 | (uintptr_t)W1 | (uintptr_t)dst) & 15) return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
-  const int64_t tiles = ceil_div(rows, mode == 2 ? 128 : 256);
-  if (tiles > 65535) {
-    // grid.y is 16 bits wide: pack in runs of tiles
-    const int64_t run = 32768;
-    for (int64_t t0 = 0; t0 < tiles; t0 += run) {
-      const int64_t nt = tiles - t0 < run ? tiles - t0 : run;
-      const int64_t r0 = t0 * (mode == 2 ? 128 : 256);
-      PackArgs p;
-      p.W0 = (const u32x4*)((const char*)W0 + r0 * ld * 2);
-      p.W1 = W1 ? (const u32x4*)((const char*)W1 + r0 * ld * 2) : nullptr;
-      p.dst = (u32x4*)((char*)dst + (size_t)t0 * (K / 32) * SLICE);
-      p.ld_chunks = ld / 8; p.rows = rows - r0; p.nsl = K / 32; p.mode = mode;
-      Timed t(name, s);
-      hipLaunchKernelGGL(pack_kernel, dim3(K / 64, (unsigned)nt), dim3(256), 0, s, p);
-      MOEP_HIP(hipGetLastError());
-    }
-    return MOEP_OK;
-  }
-  PackArgs p;
-  p.W0 = (const u32x4*)W0; p.W1 = (const u32x4*)W1; p.dst = (u32x4*)dst;
-  p.ld_chunks = ld / 8; p.rows = rows; p.nsl = K / 32; p.mode = mode;
-  Timed t(name, s);
-  hipLaunchKernelGGL(pack_kernel, dim3(K / 64, (unsigned)tiles), dim3(256), 0, s, p);
-  MOEP_HIP(hipGetLastError());
-  return MOEP_OK;
-}
-
 int launch_pack_a_bf16(const void* X, int64_t ld, int64_t rows, int K, void* dst, hipStream_t s, const char* name) {
-  return launch_pack(X, nullptr, ld, rows, K, 0, dst, s, name);
+  if (ld % 8) return fail(MOEP_EUNSUPPORTED, "%s: leading dimension must be a multiple of 8", name);
+  PackArgs p = {};
+  p.W0 = (const u32x4*)X; p.dst = (u32x4*)dst; p.ld_chunks = ld / 8; p.rows = rows; p.mode = 0;
+  return launch_pack(p, ceil_div(rows, 256), K, 1, s, name);
 }
 
-int launch_pack_b_bf16(const void* W0, const void* W1, int N, int K, void* dst, hipStream_t s, const char* name) {
-  return launch_pack(W0, W1, K, N, K, W1 ? 2 : 1, dst, s, name);
+int launch_pack_a_gathered_bf16(const void* X, int64_t ld, const int32_t* rows_of, const int32_t* tile_expert,
+                                const int32_t* tile_row0, const int32_t* seg_end, const int32_t* tiles_in_use,
+                                int64_t max_tiles, int K, void* dst, hipStream_t s, const char* name) {
+  if (ld % 8) return fail(MOEP_EUNSUPPORTED, "%s: leading dimension must be a multiple of 8", name);
+  PackArgs p = {};
+  p.W0 = (const u32x4*)X; p.dst = (u32x4*)dst; p.ld_chunks = ld / 8; p.mode = 3;
+  p.rows_of = rows_of; p.tile_expert = tile_expert; p.tile_row0 = tile_row0; p.seg_end = seg_end;
+  p.tiles_in_use = tiles_in_use;
+  return launch_pack(p, max_tiles, K, 1, s, name);
+}
+
+int launch_pack_b_bf16(const void* W0, const void* W1, int N, int K, int experts, void* dst, hipStream_t s,
+                       const char* name) {
+  PackArgs p = {};
+  p.W0 = (const u32x4*)W0; p.W1 = (const u32x4*)W1; p.dst = (u32x4*)dst;
+  p.ld_chunks = K / 8; p.rows = N; p.mode = W1 ? 2 : 1;
+  p.src_expert_chunks = (int64_t)N * (K / 8);
+  p.dst_expert_chunks = (int64_t)(packed_b_bytes(N, K, W1 != nullptr) / 16);
+  return launch_pack(p, ceil_div(N, W1 ? 128 : 256), K, experts, s, name);
 }
 
 int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* name) {
@@ -423,18 +495,33 @@ int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* 
   if (g.M <= 0) return MOEP_OK;
   if (((uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C) & 15)
     return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
-  if (g.epilogue == EPI_STORE && (g.ldc % 8 || g.ldc < g.N)) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
-  KArgs k;
+  if (g.epilogue != EPI_SWIGLU && (g.ldc % 8 || g.ldc < g.N)) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
+  const bool grouped = g.tile_expert != nullptr;
+  if (grouped && (!g.tile_row0 || !g.seg_end || !g.tiles_in_use || g.max_m_tiles <= 0))
+    return fail(MOEP_EINVAL, "%s: incomplete tile map", name);
+  if (g.epilogue == EPI_ROWSCALE_F32 && !g.row_scale) return fail(MOEP_EINVAL, "%s: row_scale is NULL", name);
+  KArgs k = {};
   k.A = (const char*)g.A; k.B = (const char*)g.B; k.C = g.C;
   k.M = g.M; k.ldc = g.ldc; k.N = g.N; k.nsl = g.K / 32;
-  const int64_t m_tiles = ceil_div(g.M, 256);
+  k.tile_expert = g.tile_expert; k.tile_row0 = g.tile_row0; k.seg_end = g.seg_end; k.tiles_in_use = g.tiles_in_use;
+  k.b_expert_bytes = (int64_t)packed_b_bytes(g.N, g.K, g.epilogue == EPI_SWIGLU);
+  k.row_scale = g.row_scale;
+  const int64_t m_tiles = grouped ? g.max_m_tiles : ceil_div(g.M, 256);
   const int64_t n_tiles = ceil_div(g.N, g.epilogue == EPI_SWIGLU ? 128 : 256);
   if (m_tiles * n_tiles >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "%s: too many tiles", name);
   k.m_tiles = (int)m_tiles; k.n_tiles = (int)n_tiles;
   Timed t(name, s);
-  switch (g.epilogue) {
-    case EPI_STORE: return launch<EPI_STORE>(k, s);
-    case EPI_SWIGLU: return launch<EPI_SWIGLU>(k, s);
+  if (grouped) {
+    switch (g.epilogue) {
+      case EPI_STORE: return launch<EPI_STORE, true>(k, s);
+      case EPI_SWIGLU: return launch<EPI_SWIGLU, true>(k, s);
+      case EPI_ROWSCALE_F32: return launch<EPI_ROWSCALE_F32, true>(k, s);
+    }
+  } else {
+    switch (g.epilogue) {
+      case EPI_STORE: return launch<EPI_STORE, false>(k, s);
+      case EPI_SWIGLU: return launch<EPI_SWIGLU, false>(k, s);
+    }
   }
   return fail(MOEP_EINVAL, "%s: unsupported epilogue %d", name, g.epilogue);
 }

@@ -320,7 +320,17 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p
   p->off_seg_end = take((size_t)E * 4);
   p->off_tile_expert = take((size_t)(p->max_tiles + 1) * 4);   // + the count of tiles in use
   p->off_tile_row0 = take((size_t)p->max_tiles * 4);
-  p->off_h = take((size_t)p->max_slots * F * dtype_size(dt));
+  if (dt == MOEP_BF16) {
+    // packed-operand GEMMs: h and the gathered x hold one 256-row block per tile; every expert's weights
+    // are re-laid out once per call
+    p->off_h = take(packed_a_bytes(p->max_tiles * GEMM_BM, F));
+    p->off_xp = take(packed_a_bytes(p->max_tiles * GEMM_BM, H));
+    p->off_w13 = take((size_t)E * packed_b_bytes(F, H, true));
+    p->off_w2 = take((size_t)E * packed_b_bytes(H, F, false));
+  } else {
+    p->off_h = take((size_t)p->max_slots * F * dtype_size(dt));
+    p->off_xp = p->off_w13 = p->off_w2 = 0;
+  }
   p->off_slot_out = take(with_slot_out ? (size_t)p->max_slots * H * 4 : 0);
   p->total = off > 0 ? off : 256;
   return MOEP_OK;
