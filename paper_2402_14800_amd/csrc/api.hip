@@ -99,9 +99,6 @@ static int check_ws(const void* ws, size_t ws_bytes, size_t need, const char* wh
   return MOEP_OK;
 }
 
-static int run_gemm(const GemmArgs& g, moep_dtype dt, hipStream_t s, const char* name) {
-  return dt == MOEP_BF16 ? launch_gemm_bf16(g, s, name) : launch_gemm_f32(g, s, name);
-}
 
 }  // namespace moep
 
@@ -242,14 +239,14 @@ int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const v
     up.C = ws; up.ldc = F;
     up.M = T; up.N = F; up.K = H;
     up.epilogue = EPI_SWIGLU;
-    if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu")) return st;
+    if (int st = launch_gemm_f32(up, s, "gemm_gate_up_swiglu")) return st;
     GemmArgs down;                                // Y[e] = h W2[e]^T
     down.A = ws; down.lda = F;
     down.B0 = (const char*)W2 + (size_t)e * H * F * es;
     down.C = (char*)Y + (size_t)e * T * H * es; down.ldc = H;
     down.M = T; down.N = H; down.K = F;
     down.epilogue = EPI_STORE;
-    if (int st = run_gemm(down, dt, s, "gemm_down")) return st;
+    if (int st = launch_gemm_f32(down, s, "gemm_down")) return st;
   }
   return MOEP_OK;
 }
@@ -323,7 +320,7 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
   up.seg_end = (const int32_t*)(w + p.off_seg_end);
   up.max_m_tiles = p.max_tiles;
   up.tiles_in_use = up.tile_expert + p.max_tiles;
-  if (int st = run_gemm(up, dt, s, "gemm_gate_up_swiglu_routed")) return st;
+  if (int st = launch_gemm_f32(up, s, "gemm_gate_up_swiglu_routed")) return st;
 
   GemmArgs down;                    // slot_out[slot] = weight(slot) * h[slot] W2[e]^T, fp32
   down.A = w + p.off_h; down.lda = F;
@@ -335,7 +332,7 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
   down.tile_expert = up.tile_expert; down.tile_row0 = up.tile_row0; down.seg_end = up.seg_end;
   down.max_m_tiles = p.max_tiles;
   down.tiles_in_use = up.tiles_in_use;
-  return run_gemm(down, dt, s, "gemm_down_routed");
+  return launch_gemm_f32(down, s, "gemm_down_routed");
 }
 
 size_t moe_forward_skip_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {

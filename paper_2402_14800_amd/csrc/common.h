@@ -34,7 +34,7 @@ static inline size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t dtype_size(moep_dtype dt) { return dt == MOEP_BF16 ? 2 : 4; }
 
-// ---- GEMM: C = epilogue(A B^T), A [M,K] and B [N,K] both K-contiguous ---------
+// ---- fp32 GEMM: C = epilogue(A B^T), A [M,K] and B [N,K] both K-contiguous, row-major operands -----
 enum GemmEpilogue {
   EPI_STORE = 0,      // C[m,n] = acc                       (C in dt, N columns)
   EPI_SWIGLU = 1,     // C[m,n] = silu(A B0^T) * (A B1^T)    (C in dt, N columns)
@@ -66,7 +66,6 @@ struct GemmArgs {
 
 constexpr int GEMM_BM = 256;   // rows per tile of either GEMM implementation's grouped map
 
-int launch_gemm_bf16(const GemmArgs& g, hipStream_t s, const char* name);
 int launch_gemm_f32(const GemmArgs& g, hipStream_t s, const char* name);
 
 // ---- bf16 GEMM on packed operands (dense expert pass) ---------------------------------
