@@ -152,6 +152,8 @@ EXPERT_CASES = [
     ("bf16", 2, 128, 192, 300),      # ragged M tile, N tail in both GEMMs
     ("bf16", 3, 256, 320, 257),      # one row into a second M tile
     ("bf16", 2, 512, 1024, 1000),
+    ("bf16", 1, 64, 64, 76837),      # more tiles than compute units, K shorter than the load-ahead distance
+    ("bf16", 2, 192, 448, 66000),    # several tiles per workgroup in both GEMMs, ragged last tile
 ]
 
 
