@@ -243,21 +243,35 @@ def main():
         def forward(b):
             pkg.moe_forward_skip(x_skip, Wg, W1, W3, W2, b, workspace=ws_skip, want_logits=False, want_top2=False)
 
-        def timed_forward(b):
-            forward(b)
+        def timed_forward(fn, b):
+            fn(b)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(args.steps):
-                forward(b)
+                fn(b)
             torch.cuda.synchronize()
             return 1e3 * (time.perf_counter() - t0) / args.steps
 
-        unskipped_ms = timed_forward(0.0)
-        skipped_ms = timed_forward(beta)
+        unskipped_ms = timed_forward(forward, 0.0)
+        skipped_ms = timed_forward(forward, beta)
+        # the same two on expert weights packed once, outside the timed region (a serving loop's case)
+        packed = pkg.moe_pack_weights(W1, W3, W2)
+
+        def forward_packed(b):
+            pkg.moe_forward_pruned_skip_packed(x_skip, Wg, packed, F, b, workspace=ws_skip, want_logits=False,
+                                               want_top2=False)
+
+        unskipped_packed_ms = timed_forward(forward_packed, 0.0)
+        skipped_packed_ms = timed_forward(forward_packed, beta)
+        del packed
         out["skip_forward_vs_unskipped"] = {"tokens": T_skip, "unskipped_ms": unskipped_ms, "skipped_ms": skipped_ms,
                                             "speedup": unskipped_ms / skipped_ms,
                                             "unskipped_tokens_per_s": T_skip / (unskipped_ms * 1e-3),
-                                            "skipped_tokens_per_s": T_skip / (skipped_ms * 1e-3)}
+                                            "skipped_tokens_per_s": T_skip / (skipped_ms * 1e-3),
+                                            "prepacked_weights": {
+                                                "unskipped_ms": unskipped_packed_ms, "skipped_ms": skipped_packed_ms,
+                                                "speedup": unskipped_packed_ms / skipped_packed_ms,
+                                                "skipped_tokens_per_s": T_skip / (skipped_packed_ms * 1e-3)}}
     n_rank_needed = max(min(E, min(k, r) + E - r) for r in cfg.rs)
     # (not with a harness-side logit bias: the rank-limited pass ranks by its own router logits)
     if not args.no_rank_limited and n_rank_needed <= 8 and bias is None:

@@ -153,6 +153,27 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
                             float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
                             void* hip_stream);
 
+/* ---- packed expert weights (serving loops) ----------------------------------- */
+/* The bf16 expert GEMMs read their operands in a blocked layout; the forward calls above re-lay
+ * the layer's expert weights out on every call (a read and a write of all of them).  A caller
+ * that runs the same layer many times (token generation with dynamic skipping, Sec. 3.3 and the
+ * speed-up table of Sec. 4) does it once:
+ *   moe_packed_weights_bytes: size of the packed copy of W1, W3, W2 (0 if dt is not MOEP_BF16 or
+ *     H, F are not multiples of 64);
+ *   moe_pack_weights: W1, W3 [E,F,H], W2 [E,H,F] -> packed (device, caller-owned, 256-byte
+ *     aligned, moe_packed_weights_bytes bytes); asynchronous on hip_stream;
+ *   moe_forward_pruned_skip_packed: moe_forward_pruned_skip with `packed_weights` in place of
+ *     W1, W3, W2; same outputs bit for bit, same workspace (moe_forward_skip_workspace).
+ * MOEP_EUNSUPPORTED for MOEP_F32 (fp32 storage has no packed form). */
+size_t moe_packed_weights_bytes(int E, int H, int F, moep_dtype dt);
+int moe_pack_weights(const void* W1, const void* W3, const void* W2, int E, int H, int F,
+                     moep_dtype dt, void* packed, void* hip_stream);
+int moe_forward_pruned_skip_packed(const void* x, const void* Wgate, const void* packed_weights,
+                                   int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                                   uint32_t kept_mask, float beta, void* out, uint8_t* skip_mask,
+                                   float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
+                                   void* hip_stream);
+
 /* ---- moe_forward_skip_topk -------------------------------------------------- */
 /* Dynamic skipping for top-k routing, 1 <= k <= 16 (appendix on the theory of dynamic skipping).
  * Per token, with w_1 >= ... >= w_k the Eq. 1 weights of its top-k experts among `kept_mask`

@@ -25,6 +25,7 @@ EXPORTS = (
     "moe_expert_outputs_workspace", "moe_expert_outputs",
     "prune_enumerate_workspace", "prune_enumerate",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
+    "moe_packed_weights_bytes", "moe_pack_weights", "moe_forward_pruned_skip_packed",
     "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
     "skip_calibrate_beta_workspace", "skip_calibrate_beta", "expert_selection_stats",
     "moe_expert_outputs_ranked_workspace", "moe_expert_outputs_ranked", "prune_enumerate_ranked",
@@ -76,6 +77,14 @@ def _load() -> ctypes.CDLL:
     lib.moe_forward_pruned_skip.argtypes = [c_void_p] * 5 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_uint32,
                                                              c_float, c_void_p, c_void_p, c_void_p, c_void_p,
                                                              c_void_p, c_size_t, c_void_p]
+    lib.moe_packed_weights_bytes.restype = c_size_t
+    lib.moe_packed_weights_bytes.argtypes = [c_int, c_int, c_int, c_int]
+    lib.moe_pack_weights.restype = c_int
+    lib.moe_pack_weights.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+    lib.moe_forward_pruned_skip_packed.restype = c_int
+    lib.moe_forward_pruned_skip_packed.argtypes = [c_void_p] * 3 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_uint32,
+                                                                    c_float, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                                    c_void_p, c_size_t, c_void_p]
     lib.moe_forward_skip_topk_workspace.restype = c_size_t
     lib.moe_forward_skip_topk_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, c_int]
     lib.moe_forward_skip_topk.restype = c_int
@@ -290,6 +299,42 @@ def moe_forward_skip(x, Wgate, W1, W3, W2, beta: float, k: int = 2, workspace=No
 
 def moe_forward_pruned_skip(x, Wgate, W1, W3, W2, kept_mask: int, beta: float, **kw):
     return moe_forward_skip(x, Wgate, W1, W3, W2, beta, kept_mask=kept_mask, **kw)
+
+
+def moe_pack_weights(W1, W3, W2) -> torch.Tensor:
+    """The layer's expert weights in the layout the bf16 GEMMs read (uint8 tensor, for *_packed calls)."""
+    dev = _dev(W1, W3, W2)
+    dt = _dtype_code(W1)
+    E, F, H = W1.shape
+    assert W3.shape == (E, F, H) and W2.shape == (E, H, F)
+    need = int(_lib.moe_packed_weights_bytes(E, H, F, dt))
+    if need == 0:
+        raise MoepError(2, "moe_pack_weights: bf16 weights with H and F multiples of 64 only")
+    packed = torch.empty((need,), dtype=torch.uint8, device=dev)
+    _check(_lib.moe_pack_weights(_ptr(W1), _ptr(W3), _ptr(W2), E, H, F, dt, _ptr(packed), _stream(dev)))
+    return packed
+
+
+def moe_forward_pruned_skip_packed(x, Wgate, packed, F: int, beta: float, kept_mask: Optional[int] = None,
+                                   k: int = 2, workspace=None, want_logits: bool = True, want_top2: bool = True):
+    """moe_forward_pruned_skip on weights packed once by moe_pack_weights."""
+    dev = _dev(x, Wgate, packed)
+    dt = _dtype_code(x)
+    T, H = x.shape
+    E = Wgate.shape[0]
+    assert Wgate.shape == (E, H) and packed.numel() == int(_lib.moe_packed_weights_bytes(E, H, F, dt))
+    if kept_mask is None:
+        kept_mask = (1 << E) - 1
+    out = torch.empty((T, H), dtype=x.dtype, device=dev)
+    skip = torch.empty((T,), dtype=torch.uint8, device=dev)
+    logits = torch.empty((T, E), dtype=torch.float32, device=dev) if want_logits else None
+    top2 = torch.empty((T, 2), dtype=torch.int32, device=dev) if want_top2 else None
+    need = _lib.moe_forward_skip_workspace(T, E, H, F, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.moe_forward_pruned_skip_packed(_ptr(x), _ptr(Wgate), _ptr(packed), T, E, H, F, dt, k,
+                                               c_uint32(kept_mask), c_float(beta), _ptr(out), _ptr(skip),
+                                               _ptr(logits), _ptr(top2), _ptr(ws), ws.numel(), _stream(dev)))
+    return out, skip, logits, top2
 
 
 def moe_forward_skip_topk(x, Wgate, W1, W3, W2, k: int, beta: float, kept_mask: Optional[int] = None,

@@ -281,7 +281,8 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
 // With `plain_out` the down projection instead stores the unscaled expert output of every slot there,
 // in the storage dtype.
 static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, const void* W3,
-                          const void* W2, moep_dtype dt, char* w, hipStream_t s, void* plain_out = nullptr) {
+                          const void* W2, moep_dtype dt, char* w, hipStream_t s, void* plain_out = nullptr,
+                          const void* packed = nullptr) {
   const int H = p.H, F = p.F;
   if (dt == MOEP_BF16) {
     // Packed-operand path: the routed rows of x are gathered into one 256-row block per tile, every
@@ -293,16 +294,23 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
     const int32_t* tiles_in_use = tile_expert + p.max_tiles;
     if (int st = launch_pack_a_gathered_bf16(x, H, slot_token, tile_expert, tile_row0, seg_end, tiles_in_use,
                                              p.max_tiles, H, w + p.off_xp, s, "pack_x_routed")) return st;
-    if (int st = launch_pack_b_bf16(W1, W3, F, H, p.E, w + p.off_w13, s, "pack_w")) return st;
-    if (int st = launch_pack_b_bf16(W2, nullptr, H, F, p.E, w + p.off_w2, s, "pack_w")) return st;
+    const char* w13 = w + p.off_w13;
+    const char* w2 = w + p.off_w2;
+    if (packed) {                     // packed once by moe_pack_weights: all W1/W3 pairs, then all W2
+      w13 = (const char*)packed;
+      w2 = w13 + (size_t)p.E * packed_b_bytes(F, H, true);
+    } else {
+      if (int st = launch_pack_b_bf16(W1, W3, F, H, p.E, w + p.off_w13, s, "pack_w")) return st;
+      if (int st = launch_pack_b_bf16(W2, nullptr, H, F, p.E, w + p.off_w2, s, "pack_w")) return st;
+    }
     PackedGemmArgs up;
-    up.A = w + p.off_xp; up.B = w + p.off_w13; up.C = w + p.off_h;
+    up.A = w + p.off_xp; up.B = w13; up.C = w + p.off_h;
     up.M = p.max_slots; up.N = F; up.K = H; up.epilogue = EPI_SWIGLU;
     up.tile_expert = tile_expert; up.tile_row0 = tile_row0; up.seg_end = seg_end; up.tiles_in_use = tiles_in_use;
     up.max_m_tiles = p.max_tiles;
     if (int st = launch_gemm_bf16_packed(up, s, "gemm_gate_up_swiglu_routed")) return st;
     PackedGemmArgs down = up;
-    down.A = w + p.off_h; down.B = w + p.off_w2;
+    down.A = w + p.off_h; down.B = w2;
     down.C = plain_out ? plain_out : w + p.off_slot_out; down.ldc = H;
     down.N = H; down.K = F;
     down.epilogue = plain_out ? EPI_STORE : EPI_ROWSCALE_F32;
@@ -351,11 +359,12 @@ int moe_forward_skip(const void* x, const void* Wgate, const void* W1, const voi
                                  logits_out, top2_out, ws, ws_bytes, hip_stream);
 }
 
-int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
-                            const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
-                            uint32_t kept_mask, float beta, void* out, uint8_t* skip_mask,
-                            float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
-                            void* hip_stream) {
+// `packed` != NULL: the expert weights as re-laid out by moe_pack_weights (W1, W3, W2 are not read).
+static int forward_pruned_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
+                               const void* W2, const void* packed, int64_t T, int E, int H, int F,
+                               moep_dtype dt, int k, uint32_t kept_mask, float beta, void* out,
+                               uint8_t* skip_mask, float* logits_out, int32_t* top2_out, void* ws,
+                               size_t ws_bytes, void* hip_stream) {
   const char* who = "moe_forward_skip";
   if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
   if (k != 2) return fail(MOEP_EUNSUPPORTED, "%s: only k = 2 is implemented (k=%d)", who, k);
@@ -364,7 +373,8 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
   if (__builtin_popcount(kept_mask) < 2) return fail(MOEP_EINVAL, "%s: kept_mask 0x%x keeps fewer than two experts", who, kept_mask);
   if (!(beta >= 0.0f) || std::isinf(beta)) return fail(MOEP_EINVAL, "%s: beta must be finite and >= 0", who);
   if (int st = check_alignment(H, F, dt, who)) return st;
-  if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (!Wgate || (!packed && (!W1 || !W3 || !W2))) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (packed && dt != MOEP_BF16) return fail(MOEP_EUNSUPPORTED, "%s: packed weights exist for bf16 only", who);
   if (T == 0) return MOEP_OK;
   if (!x || !out || !skip_mask) return fail(MOEP_EINVAL, "%s: NULL x, out or skip_mask", who);
   SkipPlan p;
@@ -378,9 +388,49 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   if (int st = launch_skip_routing(p, logits, kept_mask, beta, skip_mask, top2_out, w, s)) return st;
 
-  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s)) return st;
+  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s, nullptr, packed)) return st;
   (void)es;
   return launch_skip_combine(p, dt, skip_mask, out, w, s);
+}
+
+int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
+                            const void* W2, int64_t T, int E, int H, int F, moep_dtype dt, int k,
+                            uint32_t kept_mask, float beta, void* out, uint8_t* skip_mask,
+                            float* logits_out, int32_t* top2_out, void* ws, size_t ws_bytes,
+                            void* hip_stream) {
+  return forward_pruned_skip(x, Wgate, W1, W3, W2, nullptr, T, E, H, F, dt, k, kept_mask, beta, out, skip_mask,
+                             logits_out, top2_out, ws, ws_bytes, hip_stream);
+}
+
+// ------------------------------------------------------------------ packed weights for serving loops
+size_t moe_packed_weights_bytes(int E, int H, int F, moep_dtype dt) {
+  if (!valid_shape(1, E, H, F, dt, "moe_packed_weights_bytes")) return 0;
+  if (dt != MOEP_BF16 || check_alignment(H, F, dt, "moe_packed_weights_bytes")) return 0;
+  return (size_t)E * (packed_b_bytes(F, H, true) + packed_b_bytes(H, F, false));
+}
+
+int moe_pack_weights(const void* W1, const void* W3, const void* W2, int E, int H, int F, moep_dtype dt,
+                     void* packed, void* hip_stream) {
+  const char* who = "moe_pack_weights";
+  if (!valid_shape(1, E, H, F, dt, who)) return MOEP_EINVAL;
+  if (dt != MOEP_BF16) return fail(MOEP_EUNSUPPORTED, "%s: packed weights exist for bf16 only", who);
+  if (int st = check_alignment(H, F, dt, who)) return st;
+  if (!W1 || !W3 || !W2 || !packed) return fail(MOEP_EINVAL, "%s: NULL pointer", who);
+  if ((uintptr_t)packed & 255) return fail(MOEP_EINVAL, "%s: packed buffer must be 256-byte aligned", who);
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* w13 = (char*)packed;
+  char* w2 = w13 + (size_t)E * packed_b_bytes(F, H, true);
+  if (int st = launch_pack_b_bf16(W1, W3, F, H, E, w13, s, "pack_w")) return st;
+  return launch_pack_b_bf16(W2, nullptr, H, F, E, w2, s, "pack_w");
+}
+
+int moe_forward_pruned_skip_packed(const void* x, const void* Wgate, const void* packed_weights, int64_t T,
+                                   int E, int H, int F, moep_dtype dt, int k, uint32_t kept_mask, float beta,
+                                   void* out, uint8_t* skip_mask, float* logits_out, int32_t* top2_out,
+                                   void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!packed_weights) return fail(MOEP_EINVAL, "moe_forward_pruned_skip_packed: packed_weights is NULL");
+  return forward_pruned_skip(x, Wgate, nullptr, nullptr, nullptr, packed_weights, T, E, H, F, dt, k, kept_mask,
+                             beta, out, skip_mask, logits_out, top2_out, ws, ws_bytes, hip_stream);
 }
 
 

@@ -406,6 +406,24 @@ def test_pruned_skip_forward_matches_oracle_and_enumeration(dtype, E, H, F, T, r
                        ref2.view(torch.int16 if dtype == "bf16" else torch.int32)) and torch.equal(sk1, sk2)
 
 
+@pytest.mark.parametrize("E,H,F,T,kept,beta", [(8, 256, 512, 900, 0b10110111, 0.5), (4, 128, 192, 300, 0b1111, 0.0),
+                                               (8, 64, 64, 5, 0b11000011, 1.5)])
+def test_forward_on_prepacked_weights_is_bit_identical(E, H, F, T, kept, beta):
+    """moe_pack_weights once + moe_forward_pruned_skip_packed = moe_forward_pruned_skip, bit for bit, call after call."""
+    cfg, layer = small_layer("bf16", E, 2, H, F, T, index=13)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("x", "Wgate", "W1", "W3", "W2")]
+    ref_out, ref_skip, ref_lg, ref_top2 = pkg.moe_forward_pruned_skip(*ws, kept, beta)
+    packed = pkg.moe_pack_weights(d["W1"], d["W3"], d["W2"])
+    for _ in range(2):
+        out, skip, lg, top2 = pkg.moe_forward_pruned_skip_packed(d["x"], d["Wgate"], packed, F, beta, kept_mask=kept)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16))
+        assert torch.equal(skip, ref_skip) and torch.equal(lg, ref_lg) and torch.equal(top2, ref_top2)
+    with pytest.raises(pkg.MoepError):
+        pkg.moe_pack_weights(d["W1"].float(), d["W3"].float(), d["W2"].float())
+
+
 # ------------------------------------------------------------------ generalised top-k skipping, beta calibration
 TOPK_CASES = [
     # dtype, E, H, F, T, k, beta, kept

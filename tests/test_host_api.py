@@ -112,6 +112,20 @@ def test_argument_errors_come_back_as_status_codes():
     assert fp(*pargs(0b1)) == 1                   # fewer than two kept experts
     assert fp(*pargs(0b1_0000_0011)) == 1         # bit beyond E = 8
     assert fp(*pargs(0b11, k=3)) == 2
+    # packed-weights variants: host-side argument checks only
+    lib = binding._lib
+    assert lib.moe_packed_weights_bytes(8, 4096, 14336, 1) == 8 * 3 * 4096 * 14336 * 2
+    assert lib.moe_packed_weights_bytes(2, 128, 192, 1) == 2 * (2 * 256 * 128 * 2 + 256 * 192 * 2)   # padded tiles
+    assert lib.moe_packed_weights_bytes(8, 64, 128, 0) == 0        # fp32 storage has no packed form
+    assert lib.moe_packed_weights_bytes(8, 100, 128, 1) == 0
+    assert lib.moe_pack_weights(one, one, one, 8, 64, 128, 0, one, None) == 2
+    assert lib.moe_pack_weights(one, None, one, 8, 64, 128, 1, one, None) == 1
+    assert lib.moe_pack_weights(one, one, one, 8, 64, 128, 1, p((1 << 20) + 16), None) == 1     # misaligned
+    fpp = lib.moe_forward_pruned_skip_packed
+    ppargs = lambda mask, **kw: (lambda a: a[:2] + a[4:])(pargs(mask, **kw))      # one pointer for W1, W3, W2
+    assert fpp(*ppargs(0b1)) == 1
+    assert fpp(*ppargs(0xff, dt=0)) == 2
+    assert fpp(*(ppargs(0xff)[:2] + [None] + ppargs(0xff)[3:])) == 1
     ft = binding._lib.moe_forward_skip_topk
     assert ft(*pargs(0xff, k=0)) == 1
     assert ft(*pargs(0xff, k=17)) == 2
