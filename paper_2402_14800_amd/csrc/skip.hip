@@ -1,5 +1,5 @@
 // Dynamic skipping, top-2 (Sec. 3.3; output per App. A.2): routing, dispatch and combine.
-// The expert FFNs themselves are the grouped GEMMs (see gemm_bf16.hip / gemm_f32.hip).
+// The expert FFNs themselves are the grouped GEMMs (see gemm_bf16_packed.hip / gemm_f32.hip).
 //
 //   route    per token: top-2 experts by logit among the kept experts (ties -> lower index), delta = l_e1 - l_e0 in fp32,
 //            skip iff delta < theta = fp32(ln beta) (theta = -inf for beta = 0), weights
