@@ -1,6 +1,8 @@
 // bf16 GEMM for gfx950 on PACKED operands: C = epilogue(A B^T), fp32 accumulate on the MFMA units
-// (v_mfma_f32_16x16x32_bf16).  Used for the dense expert pass (every expert on every token, Sec. 3.1 /
-// Sec. 3.2), where the operands are re-read many times and re-laying them out once is free.
+// (v_mfma_f32_16x16x32_bf16).  Every bf16 expert GEMM runs here: the dense pass (every expert on every
+// token, Sec. 3.1 / Sec. 3.2) and, in grouped mode, the routed rows of the skipping forward (Sec. 3.3)
+// and of the rank-limited pass.  The operands are re-read many times; re-laying them out once is
+// almost free.
 //
 // Packed layout.  A matrix X [R, K] is cut into blocks of 256 rows x 32 k-values ("slices").  Block
 // (row tile t, slice s) is 16 KB, stored contiguously at ((t * K/32) + s) * 16 KB; inside it row p
@@ -47,16 +49,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
 constexpr int THREADS = 512;
-#ifndef PK_NS
-#define PK_NS 5
-#endif
-#ifndef PK_GM_GU
-#define PK_GM_GU 8
-#endif
-#ifndef PK_GM_DN
-#define PK_GM_DN 4
-#endif
-constexpr int NS = PK_NS;                   // ring stages
+constexpr int NS = 5;                       // ring stages (4 measured the same)
 constexpr int SLICE = 256 * 64;             // one operand block: 256 rows x 32 bf16
 constexpr int STAGE = 2 * SLICE;            // A block then B block
 constexpr int LDS_BYTES = NS * STAGE;       // 160 KB
@@ -161,7 +154,7 @@ void gemm_packed_kernel(KArgs p) {
 
   // Logical tile id -> (tm, tn).  Ids i, i + 8, ... belong to XCD i % 8 (the grid is a multiple of 8 or
   // a single round); every XCD gets a contiguous run of tiles, GROUP_M M-tiles deep.
-  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? PK_GM_GU : PK_GM_DN;
+  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;   // measured: the long-K down projection prefers 4 x 8 tiles per XCD
   // weight blocks of the tile's expert
   auto b_tile = [&](int tm_, int tn_) {
     const char* b = p.B + ((size_t)tn_ * nsl) * SLICE + wave_u * 2048;
