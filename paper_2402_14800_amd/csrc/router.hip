@@ -1,6 +1,7 @@
 // Router logits l[t,e] = sum_h x[t,h] Wgate[e,h] (Sec. 3.1), fp32 result.
 //
-// Bandwidth-bound: x is read once, Wgate (E x H) stays in L1/L2.  A wavefront takes four
+// Bandwidth-bound: x is read once, Wgate (E x H) stays in L1/L2.  bf16 with E <= 16 goes through
+// router_mfma_kernel below; fp32 storage and wider layers through this kernel: a wavefront takes four
 // tokens at a time; lane l owns the h-chunks l, l + 64, ... of every row (16 bytes each), keeps
 // 4 x E partial sums and a butterfly of shuffles adds them across the lanes.  The summation
 // order for a token depends on nothing but H, so the same token gives the same bits in any batch
@@ -89,8 +90,67 @@ __global__ __launch_bounds__(256) void router_kernel(const void* __restrict__ x,
   }
 }
 
+// bf16, E <= 16: the same product on the MFMA units (the fp32 FMAs and the bf16 unpacking of the kernel
+// above cost more cycles than reading x does: 0.57 ms for 262144 x 4096 against 0.44 ms here).  A wavefront
+// takes 16 tokens; per 32 hidden units one v_mfma_f32_16x16x32_bf16 multiplies the 16 token rows with the
+// (at most 16, zero-padded) expert rows of Wgate, which stay in L1/L2.  Lane l supplies row l % 16 and
+// hidden units 8 (l / 16) .. + 7 of a slice; register v of lane l of the result is token 4 (l / 16) + v,
+// expert l % 16.  A token's sum depends on its own row and H only.  (Two tiles per wavefront sharing the
+// Wgate fragments, and 1 KB row-wise loads staged through LDS, both measured slower.)
+typedef __attribute__((ext_vector_type(8))) __bf16 r_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float r_f32x4;
+
+__global__ __launch_bounds__(256) void router_mfma_kernel(const uint4* __restrict__ x,
+                                                          const uint4* __restrict__ Wgate,
+                                                          float* __restrict__ logits, int64_t T, int E,
+                                                          int H) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 16;
+  if (t0 >= T) return;
+  const int row = lane & 15, kg = lane >> 4;
+  const int chunks = H / 8;
+  const int64_t t = t0 + row < T ? t0 + row : T - 1;
+  const uint4* xp = x + t * chunks + kg;
+  const bool w_valid = row < E;
+  const uint4* wp = Wgate + (int64_t)(w_valid ? row : 0) * chunks + kg;
+  r_f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+  const int steps = H / 32;
+  for (int s0 = 0; s0 < steps; s0 += 8) {
+    uint4 xv[8], wv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool in = s0 + i < steps;
+      xv[i] = in ? xp[(s0 + i) * 4] : make_uint4(0, 0, 0, 0);
+      wv[i] = (in && w_valid) ? wp[(s0 + i) * 4] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(r_bf16x8, xv[i]),
+                                                     __builtin_bit_cast(r_bf16x8, wv[i]), acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(r_bf16x8, xv[i + 1]),
+                                                     __builtin_bit_cast(r_bf16x8, wv[i + 1]), acc1, 0, 0, 0);
+    }
+  }
+  if (row < E) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int64_t tt = t0 + 4 * kg + v;
+      if (tt < T) logits[tt * E + row] = acc0[v] + acc1[v];
+    }
+  }
+}
+
 template <bool BF16>
 int launch_t(const void* x, const void* Wgate, int64_t T, int E, int H, float* logits, hipStream_t s) {
+  if (BF16 && E <= 16 && H % 32 == 0) {
+    const int64_t blocks = ceil_div(T, 64);
+    if (blocks < ((int64_t)1 << 31)) {
+      hipLaunchKernelGGL(router_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)x,
+                         (const uint4*)Wgate, logits, T, E, H);
+      MOEP_HIP(hipGetLastError());
+      return MOEP_OK;
+    }
+  }
   const int64_t groups = ceil_div(T, TOK);
   const unsigned blocks = (unsigned)(ceil_div(groups, 4) < 16384 ? ceil_div(groups, 4) : 16384);
   if (E <= 8) hipLaunchKernelGGL((router_kernel<BF16, 8>), dim3(blocks), dim3(256), 0, s, x, Wgate, logits, T, E, H);
