@@ -227,6 +227,19 @@ def test_moe_forward_skip_matches_oracle(dtype, E, H, F, T, beta):
         assert abs(ref_skip.mean() - 0.5) <= 1.0 / T + 1e-9
 
 
+@pytest.mark.parametrize("dtype,E,H", [("bf16", 8, 256), ("bf16", 16, 128), ("bf16", 20, 64), ("f32", 4, 64)])
+def test_router_logits_do_not_depend_on_the_batch(dtype, E, H):
+    """A token's logits are the same bits whatever batch it is in and wherever it sits in it."""
+    cfg, layer = small_layer(dtype, E, 2, H, 64, 1000, index=17)
+    d = to_dev(layer)
+    ws = [d[n] for n in ("Wgate", "W1", "W3", "W2")]
+    full, _ = pkg.moe_expert_outputs(d["x"], *ws)
+    for lo, hi in ((0, 333), (5, 905), (999, 1000), (37, 53)):
+        part, _ = pkg.moe_expert_outputs(d["x"][lo:hi].contiguous(), *ws)
+        torch.cuda.synchronize()
+        assert torch.equal(part, full[lo:hi])
+
+
 def test_skip_empty_batch_and_bad_k():
     cfg, layer = small_layer("bf16", 4, 2, 64, 128, 16, index=9)
     d = to_dev(layer)
