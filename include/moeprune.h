@@ -96,6 +96,19 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
                     int k, int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
                     int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* The same for several r at once on the same logits and Y (e.g. the paper's r = 6 and r = 4): the
+ * pass over Y that builds the per-token Gram matrices does not depend on r and runs once.
+ *   rs [n_r] (host): the subset sizes, each 1 <= r <= E
+ *   loss (out): the loss vectors one after the other, C(E, rs[0]) + C(E, rs[1]) + ... floats
+ *   argmin, argmin_mask [n_r] (out), unaffected_pairs [n_r] (out, may be NULL): as above, per r
+ * Each part is bit-identical to what prune_enumerate returns for that r. */
+size_t prune_enumerate_multi_workspace(int64_t T, int E, int H, int k, int n_r, const int* rs,
+                                       moep_dtype dt);
+int prune_enumerate_multi(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt,
+                          int k, int n_r, const int* rs, float* loss, int32_t* argmin,
+                          uint32_t* argmin_mask, int64_t* unaffected_pairs, void* ws, size_t ws_bytes,
+                          void* hip_stream);
+
 /* ---- rank-limited expert pass ---------------------------------------------- */
 /* A layer pruned to r experts routes a token to the first min(k,r) KEPT experts of its ranking
  * (Sec. 3.2); at most E - r experts are missing, so only the token's first

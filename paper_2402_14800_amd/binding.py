@@ -24,6 +24,7 @@ EXPORTS = (
     "moep_num_subsets", "moep_subset_unrank", "moep_subset_rank", "moep_last_error",
     "moe_expert_outputs_workspace", "moe_expert_outputs",
     "prune_enumerate_workspace", "prune_enumerate",
+    "prune_enumerate_multi_workspace", "prune_enumerate_multi",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_packed_weights_bytes", "moe_pack_weights", "moe_forward_pruned_skip_packed",
     "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
@@ -67,6 +68,12 @@ def _load() -> ctypes.CDLL:
     lib.prune_enumerate.restype = c_int
     lib.prune_enumerate.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
                                     c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.prune_enumerate_multi_workspace.restype = c_size_t
+    lib.prune_enumerate_multi_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, POINTER(c_int), c_int]
+    lib.prune_enumerate_multi.restype = c_int
+    lib.prune_enumerate_multi.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
+                                          POINTER(c_int), c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_size_t, c_void_p]
     lib.moe_forward_skip_workspace.restype = c_size_t
     lib.moe_forward_skip_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int]
     lib.moe_forward_skip.restype = c_int
@@ -219,6 +226,39 @@ def prune_enumerate(logits, Y, k: int, r: int, workspace=None, count_unaffected:
     _check(_lib.prune_enumerate(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
                                 _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
     return loss, argmin, amask, unaffected
+
+
+def prune_enumerate_multi_workspace(T: int, E: int, H: int, k: int, rs, dtype_code: int) -> int:
+    arr = (c_int * len(rs))(*rs)
+    return int(_lib.prune_enumerate_multi_workspace(T, E, H, k, len(rs), arr, dtype_code))
+
+
+def prune_enumerate_multi(logits, Y, k: int, rs, workspace=None, count_unaffected: bool = True):
+    """prune_enumerate for every r of `rs` with one pass over Y.  Returns a list of
+    (loss [C(E,r)], argmin [1], argmin_mask [1], unaffected_pairs [1] or None), one per r (views)."""
+    dev = _dev(logits, Y)
+    dt = _dtype_code(Y)
+    E, T, H = Y.shape
+    assert logits.shape == (T, E) and logits.dtype == torch.float32
+    rs = [int(r) for r in rs]
+    ns = [num_subsets(E, r) for r in rs]
+    if not rs or min(ns) < 0:
+        raise MoepError(1, f"rs={rs}: every r must lie in [1, E={E}]")
+    loss = torch.empty((sum(ns),), dtype=torch.float32, device=dev)
+    argmin = torch.empty((len(rs),), dtype=torch.int32, device=dev)
+    amask = torch.empty((len(rs),), dtype=torch.int32, device=dev)
+    unaffected = torch.empty((len(rs),), dtype=torch.int64, device=dev) if count_unaffected else None
+    arr = (c_int * len(rs))(*rs)
+    need = _lib.prune_enumerate_multi_workspace(T, E, H, k, len(rs), arr, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.prune_enumerate_multi(_ptr(logits), _ptr(Y), T, E, H, dt, k, len(rs), arr, _ptr(loss), _ptr(argmin),
+                                      _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
+    out, off = [], 0
+    for i, n in enumerate(ns):
+        out.append((loss[off:off + n], argmin[i:i + 1], amask[i:i + 1],
+                    unaffected[i:i + 1] if unaffected is not None else None))
+        off += n
+    return out
 
 
 def moe_expert_outputs_ranked(x, Wgate, W1, W3, W2, n_rank: int, workspace=None, out=None):

@@ -275,6 +275,47 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
                           (char*)ws, (hipStream_t)hip_stream);
 }
 
+// Several r on the same logits and Y: the Gram pass, which does not depend on r, runs once.
+size_t prune_enumerate_multi_workspace(int64_t T, int E, int H, int k, int n_r, const int* rs, moep_dtype dt) {
+  if (!valid_shape(T, E, H, 1, dt, "prune_enumerate_multi_workspace") || n_r < 1 || !rs) return 0;
+  size_t need = 0;
+  for (int i = 0; i < n_r; ++i) {
+    EnumPlan p;
+    if (plan_enumerate(T, E, H, k, rs[i], &p)) return 0;
+    need = p.total > need ? p.total : need;
+  }
+  return need;
+}
+
+int prune_enumerate_multi(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt, int k,
+                          int n_r, const int* rs, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                          int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream) {
+  const char* who = "prune_enumerate_multi";
+  if (!valid_shape(T, E, H, 1, dt, who)) return MOEP_EINVAL;
+  if (n_r < 1 || !rs) return fail(MOEP_EINVAL, "%s: need at least one r", who);
+  if (H % (dt == MOEP_BF16 ? 64 : 1))
+    return fail(MOEP_EUNSUPPORTED, "%s: H=%d must be a multiple of 64 for bf16", who, H);
+  if (!loss || !argmin || !argmin_mask) return fail(MOEP_EINVAL, "%s: NULL loss, argmin or argmin_mask", who);
+  if (T > 0 && (!logits || !Y)) return fail(MOEP_EINVAL, "%s: NULL logits or Y", who);
+  size_t need = 0;
+  for (int i = 0; i < n_r; ++i) {            // every r is checked before anything is launched
+    EnumPlan p;
+    if (int st = plan_enumerate(T, E, H, k, rs[i], &p)) return st;
+    need = p.total > need ? p.total : need;
+  }
+  if (int st = check_ws(ws, ws_bytes, need, who)) return st;
+  int64_t off = 0;
+  for (int i = 0; i < n_r; ++i) {
+    EnumPlan p;
+    plan_enumerate(T, E, H, k, rs[i], &p);
+    if (int st = launch_enumerate(p, logits, Y, dt, loss + off, argmin + i, argmin_mask + i,
+                                  unaffected_pairs ? unaffected_pairs + i : nullptr, (char*)ws,
+                                  (hipStream_t)hip_stream, nullptr, i > 0)) return st;
+    off += p.n_sub;
+  }
+  return MOEP_OK;
+}
+
 // ------------------------------------------------------------------ moe_forward_skip
 // The two grouped GEMMs of the routed path: every slot (one routed (token, expert) pair, rows grouped
 // by expert) goes through its expert, and the down projection scales it by the slot's routing weight.

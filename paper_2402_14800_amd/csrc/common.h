@@ -126,7 +126,7 @@ struct RankedSource {
 };
 int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
                      float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
-                     char* ws, hipStream_t s, const RankedSource* ranked = nullptr);
+                     char* ws, hipStream_t s, const RankedSource* ranked = nullptr, bool reuse_gram = false);
 
 // ---- skipping ---------------------------------------------------------------------
 struct SkipPlan {

@@ -499,14 +499,16 @@ static void launch_score(const EnumPlan& p, const float* rec, float* partial, ui
 
 int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep_dtype dt,
                      float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
-                     char* ws, hipStream_t s, const RankedSource* ranked) {
+                     char* ws, hipStream_t s, const RankedSource* ranked, bool reuse_gram) {
   float* G = (float*)(ws + p.off_gram);
   float* rec = (float*)(ws + p.off_rec);
   float* partial = (float*)(ws + p.off_partial);
   uint32_t* pcnt = (uint32_t*)(ws + p.off_partial_cnt);
   const int cap = capacity_for(p.n_act);
   if (p.T > 0) {
-    {
+    // The Gram matrices do not depend on r: a caller that scores several r on the same logits and Y (and the same
+    // workspace: G sits at its start whatever r is) computes them once.
+    if (!reuse_gram) {
       Timed t("gram", s);
       const unsigned per_tok_blocks = (unsigned)ceil_div(p.T, 4);
       if (ranked) {

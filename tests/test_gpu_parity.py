@@ -96,6 +96,20 @@ def test_prune_enumerate_matches_oracle(E, k, r, T, H, dtype):
     assert unaff == (T * math.comb(E - k, r - k) if r >= k else 0)
 
 
+@pytest.mark.parametrize("E,k,rs,T,H,dtype", [(8, 2, (6, 4, 8, 1), 1000, 128, "bf16"), (4, 2, (2, 3), 300, 36, "f32"),
+                                              (16, 4, (12, 14), 500, 64, "bf16")])
+def test_prune_enumerate_multi_equals_separate_calls(E, k, rs, T, H, dtype):
+    """One Gram pass shared by several r: every part bit-identical to prune_enumerate for that r."""
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, dtype, seed=321, device=DEV)
+    parts = pkg.prune_enumerate_multi(logits_t, Y_t, k, rs)
+    torch.cuda.synchronize()
+    for r, (loss, amin, amask, unaff) in zip(rs, parts):
+        l1, a1, m1, u1 = pkg.prune_enumerate(logits_t, Y_t, k, r)
+        torch.cuda.synchronize()
+        assert torch.equal(loss.view(torch.int32), l1.view(torch.int32))
+        assert torch.equal(amin, a1) and torch.equal(amask, m1) and torch.equal(unaff, u1)
+
+
 def test_prune_enumerate_is_deterministic_and_handles_empty_batch():
     logits_t, Y_t = wl.make_enumeration_inputs(8, 4096, 256, "bf16", seed=5, device=DEV)
     a = pkg.prune_enumerate(logits_t, Y_t, 2, 4)

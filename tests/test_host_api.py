@@ -112,6 +112,17 @@ def test_argument_errors_come_back_as_status_codes():
     assert fp(*pargs(0b1)) == 1                   # fewer than two kept experts
     assert fp(*pargs(0b1_0000_0011)) == 1         # bit beyond E = 8
     assert fp(*pargs(0b11, k=3)) == 2
+    # several r at once
+    rs_ok, rs_bad = (ctypes.c_int * 2)(6, 4), (ctypes.c_int * 2)(6, 9)
+    wsq = binding._lib.prune_enumerate_multi_workspace
+    assert wsq(4096, 8, 256, 2, 2, rs_ok, 1) == max(binding.prune_enumerate_workspace(4096, 8, 256, 2, r, 1) for r in (6, 4))
+    assert wsq(4096, 8, 256, 2, 2, rs_bad, 1) == 0
+    fm = binding._lib.prune_enumerate_multi
+    margs = lambda rs, n=2, ws=one, wsb=1 << 40: [one, one, 4096, 8, 256, 1, 2, n, rs, one, one, one, None, ws, wsb, None]
+    assert fm(*margs(rs_bad)) == 1
+    assert fm(*margs(rs_ok, n=0)) == 1
+    assert fm(*margs(rs_ok, ws=None)) == 3
+    assert fm(*margs(rs_ok, wsb=1024)) == 3
     # packed-weights variants: host-side argument checks only
     lib = binding._lib
     assert lib.moe_packed_weights_bytes(8, 4096, 14336, 1) == 8 * 3 * 4096 * 14336 * 2
