@@ -67,10 +67,10 @@ def cpu_baseline(cfg, layer, Y, logits, torch, wl):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    n1 = 128 if cfg.H >= 4096 else 512          # tokens through all E experts (fp64 GEMMs)
+    n1 = 512 if cfg.H >= 4096 else 1024         # tokens through all E experts (fp64 GEMMs)
     n_sub_all = sum(math.comb(cfg.E, r) for r in cfg.rs)
-    # tokens through the enumeration, all r: bounded so that the oracle needs some ten seconds
-    n2 = min(2048 if cfg.H >= 4096 else 4096, max(32, int(6e5 / n_sub_all)))
+    # tokens through the enumeration, all r: bounded so that the oracle needs ten to fifteen seconds
+    n2 = min(6144 if cfg.H >= 4096 else 8192, max(32, int(2e6 / n_sub_all)))
     x = wl.to_f64(layer["x"][:n1])
     Wg = wl.to_f64(layer["Wgate"])
     t_o1 = 0.0
