@@ -27,6 +27,7 @@
  *   - Same inputs give bitwise identical outputs (no floating-point atomics).
  *   - Shape limits: 1 <= E <= 32; T >= 0 (T = 0 is a valid empty batch);
  *     for MOEP_BF16, H and F must be multiples of 64; for MOEP_F32, multiples of 4.
+ *     x, the weights, Y and the other [.,H] arrays must be 16-byte aligned (MOEP_EUNSUPPORTED otherwise).
  */
 #ifndef MOEPRUNE_H
 #define MOEPRUNE_H
@@ -71,7 +72,8 @@ const char* moep_last_error(void);
  *   x [T,H], Wgate [E,H], W1 [E,F,H], W3 [E,F,H], W2 [E,H,F]   (dt)
  *   logits [T,E] fp32 (out), Y [E,T,H] dt (out)
  * The intermediate silu(.)*(.) is rounded to dt once, between the two GEMMs.
- * Workspace: one [T,F] dt matrix. */
+ * Workspace: MOEP_F32: one [T,F] matrix; MOEP_BF16: that matrix, a copy of x and one expert's
+ * weights, all in the blocked operand layout of the GEMMs (rows padded to a multiple of 256). */
 size_t moe_expert_outputs_workspace(int64_t T, int E, int H, int F, moep_dtype dt);
 int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3,
                        const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
