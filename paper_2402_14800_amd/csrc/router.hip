@@ -166,6 +166,7 @@ int launch_router(const void* x, const void* Wgate, int64_t T, int E, int H, moe
                   float* logits, hipStream_t s) {
   if (T <= 0) return MOEP_OK;
   if (H % (dt == MOEP_BF16 ? 8 : 4)) return fail(MOEP_EUNSUPPORTED, "router: H=%d not a multiple of the 16-byte chunk", H);
+  if (((uintptr_t)x | (uintptr_t)Wgate) & 15) return fail(MOEP_EUNSUPPORTED, "router: x and Wgate must be 16-byte aligned");
   Timed t("router_logits", s);
   return dt == MOEP_BF16 ? launch_t<true>(x, Wgate, T, E, H, logits, s)
                          : launch_t<false>(x, Wgate, T, E, H, logits, s);

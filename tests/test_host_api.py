@@ -112,6 +112,9 @@ def test_argument_errors_come_back_as_status_codes():
     assert fp(*pargs(0b1)) == 1                   # fewer than two kept experts
     assert fp(*pargs(0b1_0000_0011)) == 1         # bit beyond E = 8
     assert fp(*pargs(0b11, k=3)) == 2
+    # 16-byte alignment of x is checked on the host, before anything is launched
+    odd = p((1 << 20) + 2)
+    assert binding._lib.moe_expert_outputs(odd, one, one, one, one, 64, 8, 64, 128, 1, one, one, one, 1 << 40, None) == 2
     # several r at once
     rs_ok, rs_bad = (ctypes.c_int * 2)(6, 4), (ctypes.c_int * 2)(6, 9)
     wsq = binding._lib.prune_enumerate_multi_workspace
