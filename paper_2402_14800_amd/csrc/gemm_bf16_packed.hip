@@ -15,18 +15,23 @@
 // reordered so that the transposed accumulator tiles give each lane 8 consecutive output columns, and
 // for the gate/up projection a block holds 128 rows of W1 followed by the same 128 rows of W3.
 //
-// Kernel.  One workgroup of 512 threads (8 wavefronts, 2 along M x 4 along N) owns a 256 x 256 tile of
-// the accumulator (256 x 128 outputs in SwiGLU mode); a wavefront owns 128 x 64 = 8 x 4 MFMA tiles.
+// Kernel.  One workgroup of 256 threads (4 wavefronts, 2 along M x 2 along N, one per SIMD) owns a
+// 256 x 256 tile of the accumulator (256 x 128 outputs in SwiGLU mode); a wavefront owns 128 x 128 =
+// 8 x 8 MFMA tiles, whose 256 accumulator registers sit in the AGPR half of the wavefront's 512 registers.
 // K is walked one slice (one MFMA depth) at a time through a ring of NS = 5 LDS stages of 32 KB.  In
-// the step that multiplies slice g a wavefront also issues its 4 direct loads of slice g + NS (one per
-// 8 MFMAs, into the stage slice g just left) and reads the fragments of slice g + 1 into the other
-// half of a double-buffered fragment register set.  Loads are therefore spread evenly over the step,
-// never issued in bursts, and have NS - 2 whole steps to land: with the row-major two-stage kernel the
-// wavefronts spent a large part of every step blocked in the issue of a burst of loads that the memory
-// pipeline accepts at a fixed rate.
+// the step that multiplies slice g a wavefront also issues its 8 direct loads of slice g + NS - 1 (one
+// per 6 MFMAs, into the stage whose fragments were read two steps ago) and reads the fragments of slice
+// g + 1 into the other half of a double-buffered fragment register set: 64 MFMAs, 16 LDS reads and 8
+// loads per step.  Loads are spread evenly over the step, never issued in bursts.  The wavefronts
+// meet at a barrier every SECOND step only: before it each waits until all but its 8 newest loads have
+// landed, which covers the two slices read in the two steps that follow; the stage a step's loads
+// overwrite was last read two steps earlier, i.e. before the previous barrier.
 // Workgroups are persistent (one per compute unit) and the ring runs across tile boundaries: while the
-// last slices of a tile are multiplied and its epilogue runs, the first NS slices of the workgroup's
-// next tile are already being fetched.
+// last slices of a tile are multiplied and its epilogue runs, the first slices of the workgroup's next
+// tile are already being fetched.  The loader changes tile only BETWEEN runs of steps (a tile's steps
+// are cut where the loader, NS - 1 slices ahead, reaches the end of its tile), so the hot loop is a
+// single basic block of two steps with no tile bookkeeping in it; with a branch in the loop the
+// register allocator moved accumulators between AGPRs and VGPRs on every step.
 //
 // Epilogues.  The MFMAs take the weight fragment as first operand, so an accumulator tile is the
 // transpose of the output tile and (with the row permutation above) a lane holds 8 consecutive output
@@ -48,12 +53,13 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
-constexpr int THREADS = 512;
-constexpr int NS = 5;                       // ring stages (4 measured the same)
+constexpr int THREADS = 256;
+constexpr int NS = 5;                       // ring stages
 constexpr int SLICE = 256 * 64;             // one operand block: 256 rows x 32 bf16
 constexpr int STAGE = 2 * SLICE;            // A block then B block
 constexpr int LDS_BYTES = NS * STAGE;       // 160 KB
 static_assert(GEMM_BM == 256, "tiles are 256 rows");
+static_assert((NS - 1) % 2 == 0, "the loader must be an even number of slices ahead (steps come in pairs)");
 
 // LDS row p of a weight block holds weight row perm32(p) of the tile: inside every group of 32 rows,
 // LDS row 16 b + f is weight row 8 (f >> 2) + 4 b + (f & 3).
@@ -138,14 +144,14 @@ struct KArgs {
 };
 
 template <int EPI, bool GROUPED>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_packed_kernel(KArgs p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const int wm = wave_u >> 2, wn = wave_u & 3;
+  const int wm = wave_u >> 1, wn = wave_u & 1;
   const int nsl = p.nsl;
   // Grouped launches are sized for the largest possible tile map; only its leading entries hold work.
   const uint32_t m_tiles = GROUPED ? (uint32_t)*p.tiles_in_use : (uint32_t)p.m_tiles;
@@ -157,7 +163,7 @@ void gemm_packed_kernel(KArgs p) {
   constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;   // measured: the long-K down projection prefers 4 x 8 tiles per XCD
   // weight blocks of the tile's expert
   auto b_tile = [&](int tm_, int tn_) {
-    const char* b = p.B + ((size_t)tn_ * nsl) * SLICE + wave_u * 2048;
+    const char* b = p.B + ((size_t)tn_ * nsl) * SLICE + wave_u * 4096;
     if (GROUPED) b += (int64_t)p.tile_expert[tm_] * p.b_expert_bytes;
     return b;
   };
@@ -175,12 +181,12 @@ void gemm_packed_kernel(KArgs p) {
   };
 
   // ---- loader state (all wave-uniform) ----------------------------------------------------------
-  // A wavefront moves 2 KB of each operand block per slice: KB 2 w and 2 w + 1.
+  // A wavefront moves 4 KB of each operand block per slice: KB 4 w .. 4 w + 3.
   uint32_t L_ld = blockIdx.x;
   if (L_ld >= nblk) return;
   int tm_ld, tn_ld;
   decode(L_ld, tm_ld, tn_ld);
-  const char* a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;
+  const char* a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096;
   const char* b_ld = b_tile(tm_ld, tn_ld);
   int s_ld = 0;
   int st_ld = 0;                      // byte offset of the stage the next slice goes to
@@ -194,8 +200,8 @@ void gemm_packed_kernel(KArgs p) {
   const char* ga = a_ld + lane_off;
   const char* gb = b_ld + lane_off;
 #define MOEP_LOAD1(q)                                                                           \
-  __builtin_amdgcn_global_load_lds((gptr_t)(((q) < 2 ? ga : gb) + ((q) & 1) * 1024),            \
-      (__attribute__((address_space(3))) void*)(lds3 + st_ld + ((q) < 2 ? 0 : SLICE) + wave_u * 2048 + ((q) & 1) * 1024), 16, 0, 0);
+  __builtin_amdgcn_global_load_lds((gptr_t)(((q) < 4 ? ga : gb) + ((q) & 3) * 1024),            \
+      (__attribute__((address_space(3))) void*)(lds3 + st_ld + ((q) < 4 ? 0 : SLICE) + wave_u * 4096 + ((q) & 3) * 1024), 16, 0, 0);
   // After a slice has been issued: next slice, next stage (branch-free, so that it can be scheduled into
   // the shadow of the MFMAs).  Past the end of the workgroup's stream the loader stays on its last slice:
   // the re-reads are in bounds and land in stages nobody reads again, every step issues the same loads and
@@ -208,14 +214,14 @@ void gemm_packed_kernel(KArgs p) {
     st_ld = st_ld + STAGE == LDS_BYTES ? 0 : st_ld + STAGE;                                     \
     ga = a_ld + lane_off; gb = b_ld + lane_off;                                                 \
   }
-  // ... and, rarely, the next tile of this workgroup
+  // ... and, between runs of steps, the next tile of this workgroup
 #define MOEP_NEXT_LOAD_TILE()                                                                   \
-  if (__builtin_expect(s_ld == nsl, 0)) {                                                       \
+  if (s_ld == nsl) {                                                       \
     s_ld = 0;                                                                                   \
     L_ld += G;                                                                                  \
     if (L_ld < nblk) {                                                                          \
       decode(L_ld, tm_ld, tn_ld);                                                               \
-      a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 2048;                               \
+      a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096;                               \
       b_ld = b_tile(tm_ld, tn_ld);                                                              \
     } else {                                                                                    \
       ld_ok = false;                                                                            \
@@ -231,61 +237,58 @@ void gemm_packed_kernel(KArgs p) {
   const int frow = lane & 15, fk = lane >> 4;
   const int fpos = (fk ^ ((frow >> 2) & 3)) << 4;
   const int a_fb = (wm * 128 + frow) * 64 + fpos;
-  const int b_fb = SLICE + ((EPI == EPI_SWIGLU ? wn * 32 : wn * 64) + frow) * 64 + fpos;
+  const int b_fb = SLICE + ((EPI == EPI_SWIGLU ? wn * 64 : wn * 128) + frow) * 64 + fpos;
   int st_rd = 0;                      // byte offset of the stage the next fragment read takes
   int ra = a_fb, rb = b_fb;           // the same, added to the lane's fragment offsets
 
-  f32x4 acc[8][4];
+  f32x4 acc[8][8];
 #define MOEP_ZERO_ACC()                                                                         \
   _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                 \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
       _Pragma("unroll") for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
-  MOEP_ZERO_ACC()
-  bf16x8 fa[2][8], fb[2][4];
-  // B tile j of a wavefront: SwiGLU: gate tiles 0, 1 and up tiles 2, 3 (128 rows further) of the same
-  // 32 columns; otherwise four consecutive 16-row tiles.
+  bf16x8 fa[2][8], fb[2][8];
+  // B tile j of a wavefront: SwiGLU: gate tiles 0 .. 3 and up tiles 4 .. 7 (128 rows further) of the same
+  // 64 columns; otherwise eight consecutive 16-row tiles.
 #define MOEP_RB(slot, j)                                                                        \
-  fb[slot][j] = *(const bf16x8*)(lds + rb + (EPI == EPI_SWIGLU ? ((j) >> 1) * 8192 + ((j) & 1) * 1024 : (j) * 1024));
+  fb[slot][j] = *(const bf16x8*)(lds + rb + (EPI == EPI_SWIGLU ? ((j) >> 2) * 8192 + ((j) & 3) * 1024 : (j) * 1024));
 #define MOEP_RA(slot, i) fa[slot][i] = *(const bf16x8*)(lds + ra + (i) * 1024);
 #define MOEP_MFMA(slot)                                                                         \
   _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                 \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                               \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
       acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
   // Source order = wanted issue order (a direct load writes LDS, so the compiler keeps it ordered with
-  // the fragment reads around it): three fragment reads, one direct load, four times over, spread over
-  // the 32 MFMAs by the scheduling groups below.
+  // the fragment reads around it): two fragment reads, one direct load, eight times over, spread over
+  // the first 48 of the step's 64 MFMAs by the scheduling groups below.
 #define MOEP_READS_LOADS(slot)                                                                  \
-  MOEP_RB(slot, 0) MOEP_RB(slot, 1) MOEP_RB(slot, 2) MOEP_LOAD1(0)                              \
-  MOEP_RB(slot, 3) MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_LOAD1(1)                              \
-  MOEP_RA(slot, 2) MOEP_RA(slot, 3) MOEP_RA(slot, 4) MOEP_LOAD1(2)                              \
-  MOEP_RA(slot, 5) MOEP_RA(slot, 6) MOEP_RA(slot, 7) MOEP_LOAD1(3)
+  MOEP_RB(slot, 0) MOEP_RB(slot, 1) MOEP_LOAD1(0) MOEP_RB(slot, 2) MOEP_RB(slot, 3) MOEP_LOAD1(1) \
+  MOEP_RB(slot, 4) MOEP_RB(slot, 5) MOEP_LOAD1(2) MOEP_RB(slot, 6) MOEP_RB(slot, 7) MOEP_LOAD1(3) \
+  MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_LOAD1(4) MOEP_RA(slot, 2) MOEP_RA(slot, 3) MOEP_LOAD1(5) \
+  MOEP_RA(slot, 4) MOEP_RA(slot, 5) MOEP_LOAD1(6) MOEP_RA(slot, 6) MOEP_RA(slot, 7) MOEP_LOAD1(7)
 #define MOEP_READS(slot)                                                                        \
   MOEP_RB(slot, 0) MOEP_RB(slot, 1) MOEP_RB(slot, 2) MOEP_RB(slot, 3)                           \
+  MOEP_RB(slot, 4) MOEP_RB(slot, 5) MOEP_RB(slot, 6) MOEP_RB(slot, 7)                           \
   MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_RA(slot, 2) MOEP_RA(slot, 3)                           \
   MOEP_RA(slot, 4) MOEP_RA(slot, 5) MOEP_RA(slot, 6) MOEP_RA(slot, 7)
-  // The down projection reads its fragments early (one read per MFMA, done after 12 of the 32 MFMAs); the
-  // SwiGLU kernel, whose registers are tighter, spreads them over 24 MFMAs (the early form spills there).
+  // Three MFMAs, one fragment read, twice, then one direct load.
 #define MOEP_SCHED(LOADS)                                                                       \
-  _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                                            \
-    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
+  _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_) {                                            \
+    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);                                          \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);                                          \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, EPI == EPI_SWIGLU ? 2 : 1, 0);                  \
     if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                               \
   }
   // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, lgkmcnt in bits 11:8 (0 here), expcnt 6:4 left at 7.
-  // Loads complete in issue order, so "at most (NS - 2) * 4 outstanding" means the slice the next step
-  // reads has landed (this step's slice and NS - 2 older ones may still be in flight; stores of an
-  // epilogue only add to the count).
-  constexpr int VM_MAIN = (NS - 2) * 4;
+  // Loads complete in issue order, so "at most 8 outstanding" means that everything but the slice issued in
+  // this step has landed, in particular the two slices whose fragments are read before the next barrier
+  // (stores of an epilogue only add to the count).
+  constexpr int VM_MAIN = 8;
   constexpr int W_MAIN = 0x0070 | (VM_MAIN & 15) | ((VM_MAIN >> 4) << 14);
-  // One step: multiply the slice whose fragments are in `slot`; meanwhile fetch the slice NS ahead and read
-  // the next slice's fragments into the other slot.  The barrier at the end tells every wavefront that
-  // the next slice has landed for all of them and that all of them have read this step's fragments.
-#define MOEP_STEP(slot)                                                                         \
+  // One step: multiply the slice whose fragments are in `slot`; meanwhile fetch the slice NS - 1 ahead and
+  // read the next slice's fragments into the other slot.  The barrier at the end of every second step tells
+  // every wavefront that the next two slices have landed for all of them and that all of them have read
+  // the fragments of the two stages that the next two steps' loads overwrite.
+#define MOEP_STEP(slot, BAR)                                                                    \
   {                                                                                             \
     MOEP_READS_LOADS((slot) ^ 1)                                                                \
     MOEP_MFMA(slot)                                                                             \
@@ -294,16 +297,17 @@ void gemm_packed_kernel(KArgs p) {
     st_rd = st_rd + STAGE == LDS_BYTES ? 0 : st_rd + STAGE;                                     \
     ra = a_fb + st_rd; rb = b_fb + st_rd;                                                       \
     __builtin_amdgcn_sched_barrier(0);                                                          \
-    __builtin_amdgcn_s_waitcnt(W_MAIN);                                                         \
-    __builtin_amdgcn_s_barrier();                                                               \
+    if (BAR) {                                                                                  \
+      __builtin_amdgcn_s_waitcnt(W_MAIN);                                                       \
+      __builtin_amdgcn_s_barrier();                                                             \
+    }                                                                                           \
     __builtin_amdgcn_sched_barrier(0);                                                          \
-    MOEP_NEXT_LOAD_TILE()                                                                       \
   }
 
-  // ---- prologue: the first NS slices of this workgroup's stream ---------------------------------------
+  // ---- prologue: the first NS - 1 slices of this workgroup's stream -----------------------------------
 #pragma unroll 1
-  for (int n = 0; n < NS; ++n) {
-    MOEP_LOAD1(0) MOEP_LOAD1(1) MOEP_LOAD1(2) MOEP_LOAD1(3)
+  for (int n = 0; n < NS - 1; ++n) {
+    MOEP_LOAD1(0) MOEP_LOAD1(1) MOEP_LOAD1(2) MOEP_LOAD1(3) MOEP_LOAD1(4) MOEP_LOAD1(5) MOEP_LOAD1(6) MOEP_LOAD1(7)
     MOEP_ADVANCE_LOADER()
     MOEP_NEXT_LOAD_TILE()
   }
@@ -314,22 +318,35 @@ void gemm_packed_kernel(KArgs p) {
   st_rd = STAGE;
   ra = a_fb + st_rd; rb = b_fb + st_rd;
   __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): stage 0 is overwritten by the second step's loads, and
+  __builtin_amdgcn_s_barrier();         // no barrier separates it from these reads otherwise
+  __builtin_amdgcn_sched_barrier(0);
 
   uint32_t L_mm = blockIdx.x;
   int tm, tn;
   decode(L_mm, tm, tn);
-  int s_mm = 0;
   for (;;) {
-    MOEP_STEP(0)
-    MOEP_STEP(1)
-    s_mm += 2;
-    if (__builtin_expect(s_mm < nsl, 1)) continue;
+    MOEP_ZERO_ACC()
+    // The loader is NS - 1 slices ahead and changes tile between two runs of steps, never inside one.  K / 32
+    // and NS - 1 are even, so every run is a whole number of step pairs.
+    for (int left = nsl; left > 0;) {
+      const int run = min(left, nsl - s_ld);
+#pragma unroll 1
+      for (int s_mm = 0; s_mm < run; s_mm += 2) {
+        MOEP_STEP(0, false)
+        MOEP_STEP(1, true)
+      }
+      left -= run;
+      MOEP_NEXT_LOAD_TILE()
+    }
 
     // ---- epilogue of tile (tm, tn) ------------------------------------------------------------------
     // Register v of lane l of accumulator tile (i, j) holds output row 16 i + (l % 16) of the wavefront's
     // 128 rows and fragment row f = 4 (l / 16) + v of weight tile j; with the row permutation of the weight
     // blocks, tiles 2 P and 2 P + 1 together give the lane the 8 consecutive columns 32 P + 8 (l / 16) .. + 7.
-    const int q8 = 8 * (lane >> 4);
+    int lane_e = lane;                        // opaque copy: keeps the epilogue's address arithmetic from being
+    asm volatile("" : "+v"(lane_e));          // hoisted above the K loop, where it would cost registers
+    const int q8 = 8 * (lane_e >> 4);
     int64_t row0 = (int64_t)tm * 256, row_end = p.M;
     if (GROUPED) {
       row0 = p.tile_row0[tm];
@@ -337,11 +354,13 @@ void gemm_packed_kernel(KArgs p) {
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int prow = wm * 128 + i * 16 + (lane & 15);          // row inside the tile
+      const int prow = wm * 128 + i * 16 + (lane_e & 15);          // row inside the tile
       const int64_t r = row0 + prow;
       if (r >= row_end) continue;
       if (EPI == EPI_SWIGLU) {
-        const int n = tn * 128 + wn * 32 + q8;
+#pragma unroll
+        for (int P = 0; P < 2; ++P) {
+        const int n = tn * 128 + wn * 64 + 32 * P + q8;
         if (n < p.N) {
           bf16x2 o[4];
 #pragma unroll
@@ -349,21 +368,22 @@ void gemm_packed_kernel(KArgs p) {
             f32x2 h;
 #pragma unroll
             for (int d = 0; d < 2; ++d) {
-              const int b = c >> 1, v = 2 * (c & 1) + d;
-              const float g = acc[i][b][v], u = acc[i][2 + b][v];
+              const int b = 2 * P + (c >> 1), v = 2 * (c & 1) + d;
+              const float g = acc[i][b][v], u = acc[i][4 + b][v];
               h[d] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
             }
             o[c] = __builtin_convertvector(h, bf16x2);
           }
           // packed A operand with K = N: slice n / 32, chunk (l / 16) of row prow
           char* dst = (char*)p.C + ((size_t)tm * (p.N >> 5) + (n >> 5)) * SLICE + prow * 64 +
-                      (((lane >> 4) ^ ((prow >> 2) & 3)) << 4);
+                      (((lane_e >> 4) ^ ((prow >> 2) & 3)) << 4);
           *(u32x4*)dst = __builtin_bit_cast(u32x4, o);
+        }
         }
       } else {
 #pragma unroll
-        for (int P = 0; P < 2; ++P) {
-          const int n = tn * 256 + wn * 64 + 32 * P + q8;
+        for (int P = 0; P < 4; ++P) {
+          const int n = tn * 256 + wn * 128 + 32 * P + q8;
           if (n >= p.N) continue;
           if (EPI == EPI_STORE) {
             bf16x2 o[4];
@@ -381,12 +401,11 @@ void gemm_packed_kernel(KArgs p) {
           }
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
     L_mm += G;
     if (L_mm >= nblk) break;   // (the loads still in flight are re-reads; the wavefront ends when they are back)
     decode(L_mm, tm, tn);
-    s_mm = 0;
-    MOEP_ZERO_ACC()
   }
   __builtin_amdgcn_s_waitcnt(0x0070);   // the re-reads still in flight target this workgroup's LDS
 #undef MOEP_LOAD1
