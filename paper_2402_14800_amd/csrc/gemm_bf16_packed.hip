@@ -33,6 +33,9 @@
 // single basic block of two steps with no tile bookkeeping in it; with a branch in the loop the
 // register allocator moved accumulators between AGPRs and VGPRs on every step.
 //
+// The 32 workgroups of an XCD are kept in step, round of tiles by round of tiles, through a counter in
+// device memory (bounded wait, see round_sync).
+//
 // Epilogues.  The MFMAs take the weight fragment as first operand, so an accumulator tile is the
 // transpose of the output tile and (with the row permutation above) a lane holds 8 consecutive output
 // columns of one row: one 16-byte store.  SwiGLU mode (Sec. 3.1) forms silu(gate) * up in registers,
@@ -54,6 +57,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
 constexpr int THREADS = 256;
+constexpr int SYNC_POLLS = 64;                // bound of a workgroup's wait for the others of its XCD
 constexpr int NS = 5;                       // ring stages
 constexpr int SLICE = 256 * 64;             // one operand block: 256 rows x 32 bf16
 constexpr int STAGE = 2 * SLICE;            // A block then B block
@@ -143,6 +147,11 @@ struct KArgs {
   const float* row_scale;
 };
 
+// Round counters of the persistent workgroups, one per XCD (64 bytes apart); see round_sync in the kernel.
+// They only ever grow, by a multiple of the XCD's workgroup count per launch.  Launches that overlap on
+// one GPU share them: their workgroups may then wait for each other up to the bound, nothing else.
+__device__ unsigned int g_round_count[8 * 16];
+
 template <int EPI, bool GROUPED>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_packed_kernel(KArgs p) {
@@ -200,8 +209,8 @@ void gemm_packed_kernel(KArgs p) {
   const char* ga = a_ld + lane_off;
   const char* gb = b_ld + lane_off;
 #define MOEP_LOAD1(q)                                                                           \
-  __builtin_amdgcn_global_load_lds((gptr_t)(((q) < 4 ? ga : gb) + ((q) & 3) * 1024),            \
-      (__attribute__((address_space(3))) void*)(lds3 + st_ld + ((q) < 4 ? 0 : SLICE) + wave_u * 4096 + ((q) & 3) * 1024), 16, 0, 0);
+  __builtin_amdgcn_global_load_lds((gptr_t)((q) < 4 ? ga : gb),                                   \
+      (__attribute__((address_space(3))) void*)(lds3 + st_ld + ((q) < 4 ? 0 : SLICE) + wave_u * 4096), 16, ((q) & 3) * 1024, 0);
   // After a slice has been issued: next slice, next stage (branch-free, so that it can be scheduled into
   // the shadow of the MFMAs).  Past the end of the workgroup's stream the loader stays on its last slice:
   // the re-reads are in bounds and land in stages nobody reads again, every step issues the same loads and
@@ -215,10 +224,46 @@ void gemm_packed_kernel(KArgs p) {
     ga = a_ld + lane_off; gb = b_ld + lane_off;                                                 \
   }
   // ... and, between runs of steps, the next tile of this workgroup
+  // The workgroups of an XCD start every round of tiles together: they share operand panels through the
+  // XCD's L2 only while they walk K within a few steps of each other, and left alone they settle, from
+  // one build of this file to the next, either there or in a state where every panel is fetched about three
+  // times over (L2 hit rate 0.45 instead of 0.80, 7 % slower).  Arrivals are counted in a counter that only
+  // grows; every workgroup arrives `rounds` times per launch, so the count stays a multiple of the XCD's
+  // workgroup count from launch to launch.  The wait is bounded (SYNC_POLLS polls about a thousand cycles
+  // apart); a workgroup that ran into the bound goes on alone and polls no more in this launch.  Only the
+  // timing depends on any of this, never a result.
+  const uint32_t rounds = (nblk + G - 1) / G;
+  const uint32_t my_tiles = (nblk - blockIdx.x + G - 1) / G;
+  const bool sync_on = nblk > G && (G & 7) == 0;
+  bool poll_ok = true;
+  auto round_sync = [&](bool last) {
+    if (wave_u != 0) return;
+    unsigned int* c = &g_round_count[(blockIdx.x & 7) * 16];
+    unsigned int old_v = 0;
+    if (lane == 0)
+      old_v = __hip_atomic_fetch_add(c, last ? 1u + rounds - my_tiles : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (last || !poll_ok) return;
+    // (wave-uniform arithmetic: keeps the division's constants in scalar registers)
+    const unsigned int n = G >> 3;
+    const unsigned int target = ((unsigned int)__builtin_amdgcn_readfirstlane((int)old_v) / n + 1) * n;
+    int polls = 0;
+    for (;;) {
+      unsigned int now_v = 0;
+      if (lane == 0) now_v = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned int now = (unsigned int)__builtin_amdgcn_readfirstlane((int)now_v);
+      if ((int)(now - target) >= 0) break;
+      if (++polls >= SYNC_POLLS) { poll_ok = false; break; }
+      __builtin_amdgcn_s_sleep(16);
+    }
+  };
 #define MOEP_NEXT_LOAD_TILE()                                                                   \
-  if (s_ld == nsl) {                                                       \
+  if (s_ld == nsl) {                                                                            \
     s_ld = 0;                                                                                   \
     L_ld += G;                                                                                  \
+    if (sync_on) {                                                                              \
+      round_sync(L_ld >= nblk);                                                                 \
+      __builtin_amdgcn_s_barrier();                                                             \
+    }                                                                                           \
     if (L_ld < nblk) {                                                                          \
       decode(L_ld, tm_ld, tn_ld);                                                               \
       a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096;                               \
