@@ -25,6 +25,10 @@
  *     After a non-zero status moep_last_error() describes it.  Inputs holding
  *     NaN or Inf give unspecified results.
  *   - Same inputs give bitwise identical outputs (no floating-point atomics).
+ *   - The bf16 GEMM kernels line their persistent workgroups up through 512 bytes of counters in the
+ *     library's own device data (integer atomics on values that only grow; timing depends on them,
+ *     results never do).  Calls that overlap in time on one GPU, on different streams, share these
+ *     counters: workgroups of one call may then wait for those of the other, for a bounded time.
  *   - Shape limits: 1 <= E <= 32; T >= 0 (T = 0 is a valid empty batch);
  *     for MOEP_BF16, H and F must be multiples of 64; for MOEP_F32, multiples of 4.
  *     x, the weights, Y and the other [.,H] arrays must be 16-byte aligned (MOEP_EUNSUPPORTED otherwise).
