@@ -451,6 +451,32 @@ def test_forward_on_prepacked_weights_is_bit_identical(E, H, F, T, kept, beta):
         pkg.moe_pack_weights(d["W1"].float(), d["W3"].float(), d["W2"].float())
 
 
+def test_overlapping_calls_on_two_streams_give_the_serial_results():
+    """The bf16 GEMM kernels line their persistent workgroups up through counters that every launch on the GPU
+    shares.  Two calls that overlap on different streams may make each other wait, for a bounded time; they must
+    finish and must not change a bit of either result."""
+    E, H, F, T = 2, 256, 2048, 8192          # 512 gate/up tiles: more than one round, so the workgroups do wait
+    sets = []
+    for index in (21, 22):
+        _, layer = small_layer("bf16", E, 2, H, F, T, index=index)
+        d = to_dev(layer)
+        sets.append([d[n] for n in ("x", "Wgate", "W1", "W3", "W2")])
+    serial = [pkg.moe_expert_outputs(*ws) for ws in sets]
+    torch.cuda.synchronize()
+    need = pkg.binding.moe_expert_outputs_workspace(T, E, H, F, 1)      # 1 = bf16
+    spaces = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in sets]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for _ in range(3):
+        got = []
+        for ws, space, stream in zip(sets, spaces, streams):
+            with torch.cuda.stream(stream):
+                got.append(pkg.moe_expert_outputs(*ws, workspace=space))
+        torch.cuda.synchronize()
+        for (lg, Y), (lg0, Y0) in zip(got, serial):
+            assert torch.equal(lg, lg0) and torch.equal(Y.view(torch.int16), Y0.view(torch.int16))
+
+
 # ------------------------------------------------------------------ generalised top-k skipping, beta calibration
 TOPK_CASES = [
     # dtype, E, H, F, T, k, beta, kept
