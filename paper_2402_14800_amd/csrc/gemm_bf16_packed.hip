@@ -297,10 +297,12 @@ void gemm_packed_kernel(KArgs p) {
 #define MOEP_RB(slot, j)                                                                        \
   fb[slot][j] = *(const bf16x8*)(lds + rb + (EPI == EPI_SWIGLU ? ((j) >> 2) * 8192 + ((j) & 3) * 1024 : (j) * 1024));
 #define MOEP_RA(slot, i) fa[slot][i] = *(const bf16x8*)(lds + ra + (i) * 1024);
+  // (B fragments visited back and forth, so that only one operand changes from one MFMA to the next: 0.6 % faster)
 #define MOEP_MFMA(slot)                                                                         \
   _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                 \
-    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+    _Pragma("unroll") for (int jj = 0; jj < 8; ++jj) {                                          \
+      const int j = (i & 1) ? 7 - jj : jj;                                                      \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0); }
   // Source order = wanted issue order (a direct load writes LDS, so the compiler keeps it ordered with
   // the fragment reads around it): two fragment reads, one direct load, eight times over, spread over
   // the first 48 of the step's 64 MFMAs by the scheduling groups below.
