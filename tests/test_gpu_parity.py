@@ -168,6 +168,7 @@ EXPERT_CASES = [
     ("bf16", 2, 512, 1024, 1000),
     ("bf16", 1, 64, 64, 76837),      # more tiles than compute units, K shorter than the load-ahead distance
     ("bf16", 2, 192, 448, 66000),    # several tiles per workgroup in both GEMMs, ragged last tile
+    ("bf16", 1, 128, 320, 66000),    # several tiles per workgroup with K = 4 and 10 slices (the load-ahead distance and twice the ring)
 ]
 
 
@@ -212,6 +213,7 @@ SKIP_CASES = [
     ("bf16", 8, 128, 256, 700, 0.0),     # never skip: Eq. 2
     ("bf16", 8, 128, 256, 700, 1.5),     # always skip: top-1
     ("bf16", 5, 128, 192, 3, None),      # fewer tokens than experts: empty expert segments
+    ("bf16", 4, 128, 320, 70000, None),  # grouped GEMMs with several tiles per workgroup and short K
 ]
 
 
