@@ -223,7 +223,6 @@ void gemm_packed_kernel(KArgs p) {
     st_ld = st_ld + STAGE == LDS_BYTES ? 0 : st_ld + STAGE;                                     \
     ga = a_ld + lane_off; gb = b_ld + lane_off;                                                 \
   }
-  // ... and, between runs of steps, the next tile of this workgroup
   // The workgroups of an XCD start every round of tiles together: they share operand panels through the
   // XCD's L2 only while they walk K within a few steps of each other, and left alone they settle, from
   // one build of this file to the next, either there or in a state where every panel is fetched about three
@@ -256,6 +255,7 @@ void gemm_packed_kernel(KArgs p) {
       __builtin_amdgcn_s_sleep(16);
     }
   };
+  // ... and, between runs of steps, the next tile of this workgroup
 #define MOEP_NEXT_LOAD_TILE()                                                                   \
   if (s_ld == nsl) {                                                                            \
     s_ld = 0;                                                                                   \
@@ -317,8 +317,7 @@ void gemm_packed_kernel(KArgs p) {
   MOEP_RA(slot, 0) MOEP_RA(slot, 1) MOEP_RA(slot, 2) MOEP_RA(slot, 3)                           \
   MOEP_RA(slot, 4) MOEP_RA(slot, 5) MOEP_RA(slot, 6) MOEP_RA(slot, 7)
   // Two MFMAs, a fragment read, two MFMAs, a fragment read, two MFMAs, a direct load: never more than one
-  // memory instruction between two MFMAs (with one wavefront per SIMD every instruction that is not an
-  // MFMA competes with the MFMAs for the wavefront's issue slots; 1 % faster than 3 + read + 3 + read + load).
+  // memory instruction between two MFMAs (1 % faster than 3 + read + 3 + read + load).
 #define MOEP_SCHED(LOADS)                                                                       \
   _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_) {                                            \
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                          \
