@@ -457,7 +457,7 @@ def test_overlapping_calls_on_two_streams_give_the_serial_results():
     """The bf16 GEMM kernels line their persistent workgroups up through counters that every launch on the GPU
     shares.  Two calls that overlap on different streams may make each other wait, for a bounded time; they must
     finish and must not change a bit of either result."""
-    E, H, F, T = 2, 256, 2048, 8192          # 512 gate/up tiles: more than one round, so the workgroups do wait
+    E, H, F, T = 2, 256, 2048, 24576         # 1536 gate/up tiles = 6 rounds of 256: the workgroups line up in between
     sets = []
     for index in (21, 22):
         _, layer = small_layer("bf16", E, 2, H, F, T, index=index)
