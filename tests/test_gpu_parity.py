@@ -189,6 +189,30 @@ def test_moe_expert_outputs_matches_oracle(dtype, E, H, F, T):
                                                          Y_t.view(torch.int16 if dtype == "bf16" else torch.int32))
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        E = int(rng.integers(1, 4))
+        H = 64 * int(rng.integers(1, 9))
+        F = 64 * int(rng.integers(1, 13))
+        T = int(rng.choice([1, 15, 17, 255, 257, 511, 1025, int(rng.integers(1, 2500))]))
+        shapes.append((E, H, F, T))
+    return shapes
+
+
+@pytest.mark.parametrize("E,H,F,T", _random_shapes(8, 20240214))
+def test_moe_expert_outputs_random_shapes(E, H, F, T):
+    """Seeded random layer shapes (every multiple of 64 up to 512 x 768, ragged token counts) against the oracle."""
+    cfg, layer = small_layer("bf16", E, min(2, E), H, F, T, index=31)
+    d = to_dev(layer)
+    logits_t, Y_t = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    ref_logits, ref_Y = oracle.expert_outputs(*(wl.to_f64(layer[n]) for n in ("x", "Wgate", "W1", "W3", "W2")))
+    assert np.abs(logits_t.cpu().numpy().astype(np.float64) - ref_logits).max() <= 1e-3 * np.abs(ref_logits).max()
+    check_outputs(wl.to_f64(Y_t), ref_Y, "Y")
+
+
 def test_config1_end_to_end():
     cfg = wl.CONFIGS["C1"]
     layer = wl.make_layer(cfg, device="cpu")
