@@ -238,6 +238,9 @@ SKIP_CASES = [
     ("bf16", 8, 128, 256, 700, 1.5),     # always skip: top-1
     ("bf16", 5, 128, 192, 3, None),      # fewer tokens than experts: empty expert segments
     ("bf16", 4, 128, 320, 70000, None),  # grouped GEMMs with several tiles per workgroup and short K
+    ("bf16", 3, 192, 448, 1839, None),   # odd sizes all round
+    ("bf16", 16, 64, 704, 513, 0.3),
+    ("bf16", 2, 448, 64, 257, None),
 ]
 
 
@@ -247,7 +250,8 @@ def test_moe_forward_skip_matches_oracle(dtype, E, H, F, T, beta):
     d = to_dev(layer)
     logits_full, _ = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
     torch.cuda.synchronize()
-    if beta is None:
+    median = beta is None
+    if median:
         beta = oracle.median_skip_ratio(logits_full.cpu().numpy())
     beta = float(np.float32(beta))
     out_t, skip_t, logits_t, top2_t = pkg.moe_forward_skip(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"], beta)
@@ -263,7 +267,7 @@ def test_moe_forward_skip_matches_oracle(dtype, E, H, F, T, beta):
         assert not ref_skip.any()
     elif beta > 1.0:
         assert ref_skip.all()
-    elif T >= 100:
+    elif median and T >= 100:
         assert abs(ref_skip.mean() - 0.5) <= 1.0 / T + 1e-9
 
 
