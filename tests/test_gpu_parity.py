@@ -76,6 +76,12 @@ ENUM_CASES = [
     (12, 3, 6, 90, 64, "bf16"),
     (20, 2, 18, 70, 64, "bf16"),      # E > 16: 32-row Gram tiles
     (6, 2, 4, 1, 64, "bf16"),         # a single token
+    (16, 4, 4, 100, 64, "bf16"),      # every one of 16 rank positions can be selected (n_act = 16)
+    (16, 2, 5, 90, 64, "bf16"),       # n_act = 13: the 16-position scorer with unused positions
+    (24, 2, 3, 60, 64, "bf16"),       # n_act = 23: the 32-position scorer, 32-row Gram tiles
+    (32, 2, 31, 50, 128, "bf16"),     # the largest E
+    (8, 2, 6, 200, 576, "bf16"),      # H = 512 + 64: a second, partly filled block of hidden units in the Gram pass
+    (16, 4, 12, 77, 1088, "bf16"),    # the same with 16 rows per token
 ]
 
 
@@ -342,31 +348,55 @@ def config3():
     torch.cuda.empty_cache()
 
 
-def test_config3_expert_outputs_sampled(config3):
+def one_token_per_tile(T, tile=256):
+    """One token of every 256-row M tile of the expert GEMMs, the row inside the tile varying from tile to tile
+    (first and last rows included), so that every (M tile, N tile) of both projections is compared with the oracle."""
+    n_tiles = -(-T // tile)
+    rows = (37 * np.arange(n_tiles) + 11) % tile
+    rows[::7] = 0
+    rows[3::7] = tile - 1
+    tokens = np.minimum(tile * np.arange(n_tiles) + rows, T - 1)
+    return np.unique(np.concatenate([tokens, [0, T - 1]]))
+
+
+def test_config3_expert_outputs_one_row_per_tile(config3):
     cfg, layer, logits_t, Y_t, W64 = config3
-    rng_ = np.random.default_rng(3)
-    # a few tokens from the first and last M tile plus random ones
-    tokens = np.unique(np.concatenate([[0, 255, 256, cfg.T - 257, cfg.T - 1], rng_.choice(cfg.T, 43, replace=False)]))
-    sampled_expert_check(layer, logits_t, Y_t, torch.tensor(tokens, device=DEV), W64)
+    tokens = one_token_per_tile(cfg.T)
+    assert len(np.unique(tokens // 256)) == cfg.T // 256 == 1024
+    for part in np.array_split(tokens, 4):                   # fp64 intermediates of 256 tokens at a time
+        sampled_expert_check(layer, logits_t, Y_t, torch.tensor(part, device=DEV), W64)
+
+
+def enumeration_windows_check(logits_t, Y_t, k, r, windows, loss, unaff):
+    """Cuts the tokens at the ends of `windows` (token ranges), enumerates every piece on its own and checks
+    (a) the pieces inside `windows` against the oracle (Sec. 3.2, Eq. 3), and (b) that all pieces add up to
+    the full call's losses and unaffected-pair count, which ties the oracle-checked windows to the full call."""
+    T = logits_t.shape[0]
+    cuts = sorted({0, T} | {a for a, _ in windows} | {b for _, b in windows})
+    total = np.zeros_like(loss)
+    total_unaff = 0
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        lp, ap, _, up = run_enumerate(logits_t[a:b].contiguous(), Y_t[:, a:b].contiguous(), k, r)
+        total += lp
+        total_unaff += up
+        if (a, b) in windows:
+            ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[a:b]), wl.to_f64(Y_t[:, a:b]), k, r)
+            check_losses(lp, ref)
+            check_argmin(ap, ref, lp)
+    np.testing.assert_allclose(total, loss, rtol=2e-5)
+    assert total_unaff == unaff
 
 
 def test_config3_enumeration(config3):
     cfg, layer, logits_t, Y_t, _ = config3
-    T, half, prefix = cfg.T, cfg.T // 2 + 1024, 4096
+    T = cfg.T
+    # head, an unaligned window in the middle, and the tail
+    windows = [(0, 4096), (T // 2 + 1021, T // 2 + 1021 + 3003), (T - 4099, T)]
     for r in cfg.rs:
         loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, cfg.k, r)
         assert unaff == T * math.comb(cfg.E - cfg.k, r - cfg.k)
         assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(cfg.E, r, amin)
-        # additivity over a ragged split of the tokens (same kernels, different tilings)
-        la, _, _, ua = run_enumerate(logits_t[:half].contiguous(), Y_t[:, :half].contiguous(), cfg.k, r)
-        lb, _, _, ub = run_enumerate(logits_t[half:].contiguous(), Y_t[:, half:].contiguous(), cfg.k, r)
-        np.testing.assert_allclose(la + lb, loss, rtol=2e-5)
-        assert ua + ub == unaff
-        # the oracle on a token prefix
-        lp, ap, _, _ = run_enumerate(logits_t[:prefix].contiguous(), Y_t[:, :prefix].contiguous(), cfg.k, r)
-        ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[:prefix]), wl.to_f64(Y_t[:, :prefix]), cfg.k, r)
-        check_losses(lp, ref)
-        check_argmin(ap, ref, lp)
+        enumeration_windows_check(logits_t, Y_t, cfg.k, r, windows, loss, unaff)
         # reproducible bit for bit
         loss2, amin2, _, _ = run_enumerate(logits_t, Y_t, cfg.k, r)
         assert np.array_equal(loss, loss2) and amin == amin2
@@ -402,29 +432,45 @@ def test_config5_skip_forward_sampled(config3):
     assert int(skip0.sum().item()) == 0
 
 
-def test_config4_enumeration_stress():
+@pytest.fixture(scope="module")
+def config4():
     cfg = wl.CONFIGS["C4"]
-    E, k, H, T = cfg.E, cfg.k, cfg.H, cfg.T
-    gen = torch.Generator(device=DEV)
-    gen.manual_seed(cfg.seed)
-    bias = torch.randn((E,), generator=gen, device=DEV) * cfg.gate_bias_var ** 0.5
-    logits_t = torch.randn((T, E), generator=gen, device=DEV) + bias
-    Y_t = torch.randn((E, T, H), generator=gen, device=DEV).to(torch.bfloat16)
-    load = torch.bincount(torch.topk(logits_t, k, dim=1).indices.flatten(), minlength=E).float()
+    layer = wl.make_layer(cfg, device=DEV)
+    x, Wg, W1, W3, W2 = (layer[n] for n in ("x", "Wgate", "W1", "W3", "W2"))
+    logits_t, Y_t = pkg.moe_expert_outputs(x, Wg, W1, W3, W2)
+    torch.cuda.synchronize()
+    yield cfg, layer, logits_t, Y_t
+    del layer, logits_t, Y_t
+    torch.cuda.empty_cache()
+
+
+def test_config4_expert_outputs_one_row_per_tile(config4):
+    """The expert pass at the stress configuration's shape (16 experts, H = 2048, F = 5632, 65536 tokens: 44 and 8
+    N tiles, 64 and 176 K slices) against the oracle, one token from every M tile."""
+    cfg, layer, logits_t, Y_t = config4
+    tokens = one_token_per_tile(cfg.T)
+    assert len(np.unique(tokens // 256)) == 256
+    sampled_expert_check(layer, logits_t, Y_t, torch.tensor(tokens, device=DEV), weights_f64(layer))
+
+
+def test_config4_enumeration_stress(config4):
+    """Both r of the stress configuration on the GPU's own expert outputs, the per-expert logit bias added by the
+    harness between the two calls as the configuration says."""
+    cfg, layer, logits_t, Y_t = config4
+    E, k, T = cfg.E, cfg.k, cfg.T
+    logits_b = (logits_t + layer["bias"].to(DEV)).contiguous()
+    load = torch.bincount(torch.topk(logits_b, k, dim=1).indices.flatten(), minlength=E).float()
     assert load.max() > 1.5 * load.min()                     # experts are unequally used
-    for r, prefix in ((12, 768), (8, 192)):        # prefixes sized so the oracle needs well under a minute
-        loss, amin, amask, unaff = run_enumerate(logits_t, Y_t, k, r)
+    assert tie_free(logits_b.cpu().numpy())
+    # windows sized so that the oracle needs well under a minute per r: head, unaligned middle, tail
+    for r, (w_head, w_mid, w_tail) in ((12, (768, 517, 700)), (8, (192, 131, 150))):
+        loss, amin, amask, unaff = run_enumerate(logits_b, Y_t, k, r)
         assert len(loss) == math.comb(E, r)
         assert unaff == T * math.comb(E - k, r - k)
         assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(E, r, amin)
-        cut = T // 3 + 7
-        la, _, _, _ = run_enumerate(logits_t[:cut].contiguous(), Y_t[:, :cut].contiguous(), k, r)
-        lb, _, _, _ = run_enumerate(logits_t[cut:].contiguous(), Y_t[:, cut:].contiguous(), k, r)
-        np.testing.assert_allclose(la + lb, loss, rtol=2e-5)
-        lp, ap, _, _ = run_enumerate(logits_t[:prefix].contiguous(), Y_t[:, :prefix].contiguous(), k, r)
-        ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[:prefix]), wl.to_f64(Y_t[:, :prefix]), k, r)
-        check_losses(lp, ref)
-        check_argmin(ap, ref, lp)
+        mid = T // 3 + 7
+        windows = [(0, w_head), (mid, mid + w_mid), (T - w_tail, T)]
+        enumeration_windows_check(logits_b, Y_t, k, r, windows, loss, unaff)
 
 
 # ------------------------------------------------------------------ pruned + skipping forward
