@@ -115,6 +115,25 @@ int prune_enumerate_multi(const float* logits, const void* Y, int64_t T, int E, 
                           uint32_t* argmin_mask, int64_t* unaffected_pairs, void* ws, size_t ws_bytes,
                           void* hip_stream);
 
+/* ---- prune_enumerate_static -------------------------------------------------- */
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: prune_enumerate with no workspace argument.  The scratch
+ * memory (Gram matrices, per-token records, partial sums) is a fixed array of
+ * MOEP_STATIC_SCRATCH_BYTES in the library's own device data, one copy per GPU, held until the
+ * process ends.  Arguments and outputs as prune_enumerate, bit for bit.
+ *   - Limit: prune_enumerate_workspace(T, E, H, k, r, dt) must not exceed MOEP_STATIC_SCRATCH_BYTES
+ *     (e.g. E = 8, r = 4: about 70000 tokens; E = 16, r = 8: about 5000); beyond it the call returns
+ *     MOEP_EWORKSPACE and launches nothing.
+ *   - The call allocates and frees nothing and enqueues kernels only.  The first call on a GPU looks
+ *     the array's address up (hipGetSymbolAddress): make it outside graph capture.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race and give undefined losses.  Calls one after the other on a
+ *     stream are independent: nothing is carried over from the previous call. */
+#define MOEP_STATIC_SCRATCH_BYTES (32u << 20)
+int prune_enumerate_static(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt,
+                           int k, int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                           int64_t* unaffected_pairs, void* hip_stream);
+
 /* ---- rank-limited expert pass ---------------------------------------------- */
 /* A layer pruned to r experts routes a token to the first min(k,r) KEPT experts of its ranking
  * (Sec. 3.2); at most E - r experts are missing, so only the token's first

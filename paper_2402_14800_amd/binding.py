@@ -24,7 +24,7 @@ EXPORTS = (
     "moep_num_subsets", "moep_subset_unrank", "moep_subset_rank", "moep_last_error",
     "moe_expert_outputs_workspace", "moe_expert_outputs",
     "prune_enumerate_workspace", "prune_enumerate",
-    "prune_enumerate_multi_workspace", "prune_enumerate_multi",
+    "prune_enumerate_multi_workspace", "prune_enumerate_multi", "prune_enumerate_static",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_packed_weights_bytes", "moe_pack_weights", "moe_forward_pruned_skip_packed",
     "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
@@ -68,6 +68,9 @@ def _load() -> ctypes.CDLL:
     lib.prune_enumerate.restype = c_int
     lib.prune_enumerate.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
                                     c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.prune_enumerate_static.restype = c_int
+    lib.prune_enumerate_static.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
+                                           c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.prune_enumerate_multi_workspace.restype = c_size_t
     lib.prune_enumerate_multi_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, POINTER(c_int), c_int]
     lib.prune_enumerate_multi.restype = c_int
@@ -225,6 +228,29 @@ def prune_enumerate(logits, Y, k: int, r: int, workspace=None, count_unaffected:
     ws = _workspace(need, dev, workspace)
     _check(_lib.prune_enumerate(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
                                 _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
+    return loss, argmin, amask, unaffected
+
+
+STATIC_SCRATCH_BYTES = 32 << 20      # MOEP_STATIC_SCRATCH_BYTES of include/moeprune.h
+
+
+def prune_enumerate_static(logits, Y, k: int, r: int, out=None, count_unaffected: bool = True):
+    """prune_enumerate on the library's built-in scratch array: no workspace, nothing allocated by the call
+    when `out` carries the four output tensors (loss, argmin, argmin_mask, unaffected_pairs)."""
+    dev = _dev(logits, Y)
+    dt = _dtype_code(Y)
+    E, T, H = Y.shape
+    assert logits.shape == (T, E) and logits.dtype == torch.float32
+    if out is None:
+        n = num_subsets(E, r)
+        if n < 0:
+            raise MoepError(1, f"r={r} out of range [1, E={E}]")
+        out = (torch.empty((n,), dtype=torch.float32, device=dev), torch.empty((1,), dtype=torch.int32, device=dev),
+               torch.empty((1,), dtype=torch.int32, device=dev),
+               torch.empty((1,), dtype=torch.int64, device=dev) if count_unaffected else None)
+    loss, argmin, amask, unaffected = out
+    _check(_lib.prune_enumerate_static(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
+                                       _ptr(amask), _ptr(unaffected), _stream(dev)))
     return loss, argmin, amask, unaffected
 
 

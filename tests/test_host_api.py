@@ -214,3 +214,23 @@ def test_workload_generators_are_seeded_and_prefix_stable():
     lg2, Y2 = wl.make_enumeration_inputs(6, 50, 32, dtype="bf16", seed=3, bias_var=0.5)
     assert torch.equal(lg, lg2) and torch.equal(Y, Y2) and lg.dtype == torch.float32 and Y.dtype == torch.bfloat16
     assert np.array_equal(wl.to_f64(Y).astype(np.float32), Y.float().numpy())
+
+
+def test_static_scratch_entry_point_checks_its_limit_on_the_host():
+    """prune_enumerate_static rejects a problem whose scratch need exceeds the built-in array before it touches the
+    GPU, and the Python constant matches the header's."""
+    text = open(os.path.join(ROOT, "include", "moeprune.h")).read()
+    m = re.search(r"#define\s+MOEP_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == binding.STATIC_SCRATCH_BYTES
+    p = ctypes.c_void_p
+    T, E, H, k, r = 200000, 8, 64, 2, 4
+    assert binding.prune_enumerate_workspace(T, E, H, k, r, binding.MOEP_BF16) > binding.STATIC_SCRATCH_BYTES
+    st = binding._lib.prune_enumerate_static(p(1 << 20), p(1 << 20), T, E, H, binding.MOEP_BF16, k, r,
+                                             p(1 << 20), p(1 << 20), p(1 << 20), None, None)
+    assert st == 3 and b"scratch" in binding._lib.moep_last_error()
+    st = binding._lib.prune_enumerate_static(p(1 << 20), p(1 << 20), 100, 8, 64, binding.MOEP_BF16, 2, 9,
+                                             p(1 << 20), p(1 << 20), p(1 << 20), None, None)
+    assert st == 1                                      # r > E
+    st = binding._lib.prune_enumerate_static(p(1 << 20), p(1 << 20), 100, 8, 64, binding.MOEP_BF16, 2, 4,
+                                             None, p(1 << 20), p(1 << 20), None, None)
+    assert st == 1                                      # NULL loss
