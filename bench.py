@@ -165,8 +165,12 @@ def main():
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    timing = pkg.kernel_timing_collect()
+    records = pkg.kernel_timing_records()        # (kernel, ms) launch by launch, HIP events on the launch stream
     pkg.kernel_timing_enable(False)
+    per_launch = {}
+    for name, ms in records:
+        per_launch.setdefault(name, []).append(ms)
+    timing = {name: (float(sum(v)), len(v)) for name, v in per_launch.items()}
 
     ms_per_step = 1e3 * elapsed / args.steps
     n_sub = sum(math.comb(E, r) for r in cfg.rs)
@@ -180,21 +184,26 @@ def main():
         n_act = min(E, min(k, r) + E - r)
         return 4 * n_act + n_act * (n_act + 3) // 2 + 8
     score_ops = float(sum(math.comb(E, r) * T * pair_ops(r) for r in cfg.rs))
-    work = {   # kernel -> (bound, algorithmic flops or bytes per launch)
-        "gemm_gate_up_swiglu": ("mfma", 4.0 * T * H * F),
-        "gemm_down": ("mfma", 2.0 * T * H * F),
+    work_per_step = {   # kernel -> (bound, algorithmic flops, bytes or lane operations per STEP, all launches together)
+        "gemm_gate_up_swiglu": ("mfma", 4.0 * T * H * F * E),
+        "gemm_down": ("mfma", 2.0 * T * H * F * E),
         "gemm_gate_up_swiglu_routed": ("mfma", 4.0 * slots * H * F),
         "gemm_down_routed": ("mfma", 2.0 * slots * H * F),
         "gram": ("hbm", float(E) * T * H * es + 4.0 * T * E * E),
-        "subset_score": ("alu", score_ops / len(cfg.rs)),     # per launch, averaged over the r of this workload
+        "subset_score": ("alu", score_ops),
         "router_logits": ("hbm", None),      # launched with two different T: reported as time only
     }
     kernels = {}
     for name, (total_ms, n) in sorted(timing.items()):
         avg_ms = total_ms / n
-        entry = {"launches_per_step": n / args.steps, "avg_ms": avg_ms}
-        bound, w = work.get(name, (None, None))
+        ms_sorted = sorted(per_launch[name])
+        entry = {"launches_per_step": n / args.steps, "avg_ms": avg_ms,
+                 "median_ms": ms_sorted[len(ms_sorted) // 2] if len(ms_sorted) % 2 else
+                 0.5 * (ms_sorted[len(ms_sorted) // 2 - 1] + ms_sorted[len(ms_sorted) // 2]),
+                 "min_ms": ms_sorted[0]}
+        bound, w = work_per_step.get(name, (None, None))
         if w:
+            w = w * args.steps / n            # algorithmic work of the average launch
             if bound == "alu":
                 a = w / (avg_ms * 1e-3)
                 entry.update(bound="alu", achieved=a, peak=PEAK_ALU_LANE_OPS, unit="lane-op/s", frac=a / PEAK_ALU_LANE_OPS)
@@ -206,10 +215,25 @@ def main():
                 a = w / (avg_ms * 1e-3) / 1e9
                 entry.update(bound="hbm", achieved=a, peak=PEAK_HBM_GBS, unit="GB/s", frac=a / PEAK_HBM_GBS)
         kernels[name] = entry
+    # Empirical ceiling next to the nominal peak: the MFMA stream of the GEMM's K loop alone (no LDS, memory or
+    # barrier traffic), operand bits taken from this layer's x and W1, launches of about the dominant kernel's length.
+    sink = torch.empty((1 << 17,), dtype=torch.float32, device=dev)
+    pkg.mfma_ceiling(x, W1, 2000, sink)
+    torch.cuda.synchronize()
+    pkg.kernel_timing_enable(True)
+    pkg.kernel_timing_reset()
+    ceiling_flop = [pkg.mfma_ceiling(x, W1, 40000, sink) for _ in range(5)][0]
+    ceiling_ms = sorted(ms for name, ms in pkg.kernel_timing_records() if name == "mfma_ceiling")
+    pkg.kernel_timing_enable(False)
+    empirical_peak = ceiling_flop / (ceiling_ms[len(ceiling_ms) // 2] * 1e-3) / 1e12
     dom = kernels["gemm_gate_up_swiglu"]
     roofline = {"kernel": "gemm_gate_up_swiglu", "bound": "mfma", "achieved": dom["achieved"],
                 "peak": dom["peak"], "unit": "TFLOP/s", "frac": dom["frac"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "launches_per_step": dom["launches_per_step"], "median_ms": dom["median_ms"], "min_ms": dom["min_ms"],
+                "empirical_peak": empirical_peak, "frac_of_empirical_peak": dom["achieved"] / empirical_peak,
+                "empirical_peak_kind": "MFMA-only launch of the same loop shape on this layer's operand bits, "
+                                       "median of 5 launches of %.1f ms" % ceiling_ms[len(ceiling_ms) // 2]}
 
     gemm_ms = sum(timing[n][0] for n in ("gemm_gate_up_swiglu", "gemm_down")) / args.steps
     enum_names = ("gram", "routing_prep", "subset_score", "loss_reduce_argmin")

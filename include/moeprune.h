@@ -25,10 +25,18 @@
  *     After a non-zero status moep_last_error() describes it.  Inputs holding
  *     NaN or Inf give unspecified results.
  *   - Same inputs give bitwise identical outputs (no floating-point atomics).
- *   - The bf16 GEMM kernels line their persistent workgroups up through 512 bytes of counters in the
- *     library's own device data (integer atomics on values that only grow; timing depends on them,
- *     results never do).  Calls that overlap in time on one GPU, on different streams, share these
- *     counters: workgroups of one call may then wait for those of the other, for a bounded time.
+ *   - State the library keeps.  Host: the calling thread's last error message; per GPU, behind a
+ *     mutex, the compute-unit count and which GEMM kernels have had their LDS limit raised (so
+ *     first calls from several host threads are safe); the event pool of moep_timing_*.  Device:
+ *     512 bytes of 64-bit counters in the library's own device data, through which the persistent
+ *     workgroups of the bf16 GEMM kernels line up (integer atomics on values that only grow and
+ *     cannot wrap; timing depends on them, results never do), and the scratch array of
+ *     prune_enumerate_static.  Calls that overlap in time on one GPU, on different streams, share
+ *     the counters: workgroups of one call may then wait for those of the other, for a bounded time.
+ *     The line-up takes workgroup b to run on XCD b % 8, as this part deals workgroups out; on a
+ *     part that did otherwise it would cost time, never a result.
+ *   - Entry points may be called from several host threads at once, each on its own stream and
+ *     buffers (prune_enumerate_static excepted, see there).
  *   - Shape limits: 1 <= E <= 32; T >= 0 (T = 0 is a valid empty batch);
  *     for MOEP_BF16, H and F must be multiples of 64; for MOEP_F32, multiples of 4.
  *     x, the weights, Y and the other [.,H] arrays must be 16-byte aligned (MOEP_EUNSUPPORTED otherwise).
@@ -76,7 +84,8 @@ const char* moep_last_error(void);
  *   x [T,H], Wgate [E,H], W1 [E,F,H], W3 [E,F,H], W2 [E,H,F]   (dt)
  *   logits [T,E] fp32 (out), Y [E,T,H] dt (out)
  * The intermediate silu(.)*(.) is rounded to dt once, between the two GEMMs.
- * Workspace: MOEP_F32: one [T,F] matrix; MOEP_BF16: that matrix, a copy of x and one expert's
+ * Workspace: MOEP_F32: one [T,F] matrix; MOEP_BF16: that matrix for as many experts as go into one
+ * launch (all E of them up to 12 GiB, fewer beyond), a copy of x and a copy of every expert's
  * weights, all in the blocked operand layout of the GEMMs (rows padded to a multiple of 256). */
 size_t moe_expert_outputs_workspace(int64_t T, int E, int H, int F, moep_dtype dt);
 int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3,
@@ -202,10 +211,17 @@ int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, co
  *     aligned, moe_packed_weights_bytes bytes); asynchronous on hip_stream;
  *   moe_forward_pruned_skip_packed: moe_forward_pruned_skip with `packed_weights` in place of
  *     W1, W3, W2; same outputs bit for bit, same workspace (moe_forward_skip_workspace).
+ *   moe_expert_outputs_packed: moe_expert_outputs with `packed_weights` in place of W1, W3, W2 (a
+ *     calibration loop that pushes batch after batch through the same layer, Sec. 3.2); same outputs
+ *     bit for bit; workspace moe_expert_outputs_packed_workspace (no room for weights).
  * MOEP_EUNSUPPORTED for MOEP_F32 (fp32 storage has no packed form). */
 size_t moe_packed_weights_bytes(int E, int H, int F, moep_dtype dt);
 int moe_pack_weights(const void* W1, const void* W3, const void* W2, int E, int H, int F,
                      moep_dtype dt, void* packed, void* hip_stream);
+size_t moe_expert_outputs_packed_workspace(int64_t T, int E, int H, int F, moep_dtype dt);
+int moe_expert_outputs_packed(const void* x, const void* Wgate, const void* packed_weights, int64_t T,
+                              int E, int H, int F, moep_dtype dt, float* logits, void* Y, void* ws,
+                              size_t ws_bytes, void* hip_stream);
 int moe_forward_pruned_skip_packed(const void* x, const void* Wgate, const void* packed_weights,
                                    int64_t T, int E, int H, int F, moep_dtype dt, int k,
                                    uint32_t kept_mask, float beta, void* out, uint8_t* skip_mask,
@@ -263,6 +279,20 @@ int expert_selection_stats(const float* logits, int64_t T, int E, int k, int r, 
  * At most 8192 launches are recorded between collects; later ones go untimed. */
 int moep_timing_enable(int on);
 int moep_timing_collect(const char** names, double* total_ms, int64_t* launches, int cap);
+/* The same record launch by launch, in launch order (for medians and minima): names[i], ms[i] for
+ * up to `cap` launches; returns how many were written, or -1.  Clears the record like collect. */
+int moep_timing_records(const char** names, float* ms, int cap);
+
+/* An empirical ceiling for the bf16 GEMM kernels (for benchmarks): one launch of the MFMA stream of
+ * their K loop and nothing else -- same launch shape, instruction, accumulator tiling and order, no
+ * LDS, memory or barrier traffic -- `steps` K steps (even) per wavefront.  The operand registers are
+ * filled from `a_src` and `b_src` (DEVICE, bf16 data such as the layer's x and W1; 65536 bytes per
+ * compute unit are read from each, `src_bytes` says how many each holds), because the clock this
+ * part sustains depends on the operand bits.  `sink` (DEVICE, 256 floats per compute unit, count in
+ * `sink_floats`) receives sums nobody needs.  `flop_out` (host, may be NULL) receives the floating-
+ * point operations of the launch; time it with moep_timing_* (kernel name "mfma_ceiling"). */
+int moep_mfma_ceiling(const void* a_src, const void* b_src, size_t src_bytes, int steps, float* sink,
+                      size_t sink_floats, double* flop_out, void* hip_stream);
 
 #ifdef __cplusplus
 }

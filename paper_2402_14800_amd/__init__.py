@@ -9,11 +9,11 @@ synthetic inputs and can be imported on its own.
 _BINDING_NAMES = (
     "moe_expert_outputs", "prune_enumerate", "prune_enumerate_multi", "prune_enumerate_static",
     "moe_forward_skip", "moe_forward_pruned_skip",
-    "moe_pack_weights", "moe_forward_pruned_skip_packed",
+    "moe_pack_weights", "moe_forward_pruned_skip_packed", "moe_expert_outputs_packed",
     "moe_forward_skip_topk", "skip_calibrate_beta", "expert_selection_stats",
     "moe_expert_outputs_ranked", "prune_enumerate_ranked",
     "num_subsets", "subset_unrank", "subset_rank", "library_path", "MoepError",
-    "kernel_timing_enable", "kernel_timing_collect", "kernel_timing_reset",
+    "kernel_timing_enable", "kernel_timing_collect", "kernel_timing_reset", "kernel_timing_records", "mfma_ceiling",
 )
 
 

@@ -27,10 +27,11 @@ EXPORTS = (
     "prune_enumerate_multi_workspace", "prune_enumerate_multi", "prune_enumerate_static",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_packed_weights_bytes", "moe_pack_weights", "moe_forward_pruned_skip_packed",
+    "moe_expert_outputs_packed_workspace", "moe_expert_outputs_packed",
     "moe_forward_skip_topk_workspace", "moe_forward_skip_topk",
     "skip_calibrate_beta_workspace", "skip_calibrate_beta", "expert_selection_stats",
     "moe_expert_outputs_ranked_workspace", "moe_expert_outputs_ranked", "prune_enumerate_ranked",
-    "moep_timing_enable", "moep_timing_collect",
+    "moep_timing_enable", "moep_timing_collect", "moep_timing_records", "moep_mfma_ceiling",
 )
 
 
@@ -91,6 +92,11 @@ def _load() -> ctypes.CDLL:
     lib.moe_packed_weights_bytes.argtypes = [c_int, c_int, c_int, c_int]
     lib.moe_pack_weights.restype = c_int
     lib.moe_pack_weights.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+    lib.moe_expert_outputs_packed_workspace.restype = c_size_t
+    lib.moe_expert_outputs_packed_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int]
+    lib.moe_expert_outputs_packed.restype = c_int
+    lib.moe_expert_outputs_packed.argtypes = [c_void_p] * 3 + [c_int64, c_int, c_int, c_int, c_int,
+                                                               c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.moe_forward_pruned_skip_packed.restype = c_int
     lib.moe_forward_pruned_skip_packed.argtypes = [c_void_p] * 3 + [c_int64, c_int, c_int, c_int, c_int, c_int, c_uint32,
                                                                     c_float, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -122,6 +128,11 @@ def _load() -> ctypes.CDLL:
     lib.moep_timing_enable.argtypes = [c_int]
     lib.moep_timing_collect.restype = c_int
     lib.moep_timing_collect.argtypes = [POINTER(c_char_p), POINTER(c_double), POINTER(c_int64), c_int]
+    lib.moep_timing_records.restype = c_int
+    lib.moep_timing_records.argtypes = [POINTER(c_char_p), POINTER(c_float), c_int]
+    lib.moep_mfma_ceiling.restype = c_int
+    lib.moep_mfma_ceiling.argtypes = [c_void_p, c_void_p, c_size_t, c_int, c_void_p, c_size_t, POINTER(c_double),
+                                      c_void_p]
     return lib
 
 
@@ -381,6 +392,24 @@ def moe_pack_weights(W1, W3, W2) -> torch.Tensor:
     return packed
 
 
+def moe_expert_outputs_packed(x, Wgate, packed, F: int, logits=None, Y=None, workspace=None):
+    """moe_expert_outputs on weights packed once by moe_pack_weights."""
+    dev = _dev(x, Wgate, packed)
+    dt = _dtype_code(x)
+    T, H = x.shape
+    E = Wgate.shape[0]
+    assert Wgate.shape == (E, H) and packed.numel() == int(_lib.moe_packed_weights_bytes(E, H, F, dt))
+    if logits is None:
+        logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+    if Y is None:
+        Y = torch.empty((E, T, H), dtype=x.dtype, device=dev)
+    need = _lib.moe_expert_outputs_packed_workspace(T, E, H, F, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.moe_expert_outputs_packed(_ptr(x), _ptr(Wgate), _ptr(packed), T, E, H, F, dt, _ptr(logits), _ptr(Y),
+                                          _ptr(ws), ws.numel(), _stream(dev)))
+    return logits, Y
+
+
 def moe_forward_pruned_skip_packed(x, Wgate, packed, F: int, beta: float, kept_mask: Optional[int] = None,
                                    k: int = 2, workspace=None, want_logits: bool = True, want_top2: bool = True):
     """moe_forward_pruned_skip on weights packed once by moe_pack_weights."""
@@ -468,6 +497,29 @@ def kernel_timing_collect() -> Dict[str, Tuple[float, int]]:
     if n < 0:
         raise MoepError(4, _lib.moep_last_error().decode())
     return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+def kernel_timing_records():
+    """[(kernel name, milliseconds)] launch by launch since the last collect; waits for the GPU."""
+    cap = 8192
+    names = (c_char_p * cap)()
+    ms = (c_float * cap)()
+    n = _lib.moep_timing_records(names, ms, cap)
+    if n < 0:
+        raise MoepError(4, _lib.moep_last_error().decode())
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+
+def mfma_ceiling(a_src: torch.Tensor, b_src: torch.Tensor, steps: int, sink: Optional[torch.Tensor] = None) -> float:
+    """Enqueues the MFMA-only launch (operand bits from the two bf16 tensors) and returns its flop count."""
+    dev = _dev(a_src, b_src)
+    if sink is None:
+        sink = torch.empty((1 << 17,), dtype=torch.float32, device=dev)
+    flop = c_double(0.0)
+    nbytes = min(a_src.numel() * a_src.element_size(), b_src.numel() * b_src.element_size())
+    _check(_lib.moep_mfma_ceiling(_ptr(a_src), _ptr(b_src), nbytes, steps, _ptr(sink), sink.numel(),
+                                  ctypes.byref(flop), _stream(dev)))
+    return float(flop.value)
 
 
 def kernel_timing_reset() -> None:

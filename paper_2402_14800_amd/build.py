@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoeprune.so")
-SOURCES = ["api.hip", "router.hip", "gemm_bf16_packed.hip", "gemm_f32.hip", "enumerate.hip", "skip.hip", "calibrate.hip", "stats.hip", "no_alloc.hip"]
+SOURCES = ["api.hip", "router.hip", "gemm_bf16_packed.hip", "gemm_f32.hip", "enumerate.hip", "skip.hip", "calibrate.hip", "stats.hip", "no_alloc.hip", "mfma_ceiling.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -49,6 +49,31 @@ def build(jobs: int = 6) -> str:
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     return LIB
+
+
+def kernel_resource_usage(src: str) -> dict:
+    """Register and scratch use of every kernel of one source file, as the compiler reports it
+    (-Rpass-analysis=kernel-resource-usage): {mangled kernel name: {"VGPRs": .., "AGPRs": .., "ScratchSize": ..,
+    "VGPRs Spill": .., "SGPRs Spill": .., "Occupancy": .., "LDS Size": ..}}.  Compiles the device side only."""
+    import re
+    import tempfile
+
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [HIPCC, *FLAGS, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage", "-c",
+               os.path.join(CSRC, src), "-o", os.path.join(tmp, "dev.o")]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {src}:\n{r.stderr}")
+    usage, cur = {}, None
+    for line in r.stderr.splitlines():
+        m = re.search(r"remark:\s+Function Name:\s+(\S+)", line)
+        if m:
+            cur = usage.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z ]+?)(?: \[[^\]]*\])?:\s+(\d+)", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = int(m.group(2))
+    return usage
 
 
 if __name__ == "__main__":

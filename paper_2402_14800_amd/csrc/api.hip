@@ -185,48 +185,110 @@ int moep_timing_collect(const char** names, double* total_ms, int64_t* launches,
   return n;
 }
 
+int moep_timing_records(const char** names, float* ms, int cap) {
+  TimingState& t = g_timing;
+  std::lock_guard<std::mutex> lk(t.mu);
+  if (!names || !ms || cap <= 0) {
+    fail(MOEP_EINVAL, "moep_timing_records: NULL array or cap <= 0");
+    return -1;
+  }
+  int n = 0;
+  for (int i = 0; i < t.next; ++i) {
+    auto& r = t.pool[i];
+    if (!r.used) continue;
+    r.used = false;
+    float v = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&v, r.start, r.stop) != hipSuccess) {
+      fail(MOEP_EHIP, "moep_timing_records: event query failed for %s", r.name);
+      t.next = 0;
+      return -1;
+    }
+    if (n < cap) { names[n] = r.name; ms[n] = v; ++n; }
+  }
+  t.next = 0;
+  return n;
+}
+
 // ------------------------------------------------------------------ moe_expert_outputs
+// bf16: how many experts go into one launch of each projection.  One launch per projection over ALL experts
+// saves the fill and drain of the persistent kernel per expert (what matters when a launch takes a
+// millisecond or two), at the price of holding every expert's h at once; beyond kBatchedHBytes of h the
+// experts are taken in batches that fit.
+static constexpr size_t kBatchedHBytes = (size_t)12 << 30;
+static int experts_per_launch(int64_t T, int E, int F) {
+  const size_t per = packed_a_bytes(T, F);
+  if (per == 0) return E;
+  const size_t fit = kBatchedHBytes / per;
+  return fit < 1 ? 1 : (fit > (size_t)E ? E : (int)fit);
+}
+
+static size_t expert_outputs_workspace_bf16(int64_t T, int E, int H, int F, bool weights_prepacked) {
+  size_t need = align256((size_t)experts_per_launch(T, E, F) * packed_a_bytes(T, F)) + align256(packed_a_bytes(T, H));
+  if (!weights_prepacked)
+    need += align256((size_t)E * packed_b_bytes(F, H, true)) + align256((size_t)E * packed_b_bytes(H, F, false));
+  return need;
+}
+
 size_t moe_expert_outputs_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {
   if (!valid_shape(T, E, H, F, dt, "moe_expert_outputs_workspace")) return 0;
-  if (dt == MOEP_BF16)   // packed h, packed x, one expert's packed W1/W3 pair and packed W2
-    return align256(packed_a_bytes(T, F)) + align256(packed_a_bytes(T, H)) +
-           align256(packed_b_bytes(F, H, true)) + align256(packed_b_bytes(H, F, false));
+  if (dt == MOEP_BF16)   // packed h of one batch of experts, packed x, every expert's packed W1/W3 pair and packed W2
+    return expert_outputs_workspace_bf16(T, E, H, F, false);
   return align256((size_t)T * (size_t)F * dtype_size(dt));
 }
 
-int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3,
-                       const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
-                       float* logits, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
-  const char* who = "moe_expert_outputs";
+size_t moe_expert_outputs_packed_workspace(int64_t T, int E, int H, int F, moep_dtype dt) {
+  if (!valid_shape(T, E, H, F, dt, "moe_expert_outputs_packed_workspace")) return 0;
+  if (dt != MOEP_BF16 || check_alignment(H, F, dt, "moe_expert_outputs_packed_workspace")) return 0;
+  return expert_outputs_workspace_bf16(T, E, H, F, true);
+}
+
+// `packed` != NULL: the expert weights as re-laid out by moe_pack_weights (W1, W3, W2 are not read).
+static int expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3, const void* W2,
+                          const void* packed, int64_t T, int E, int H, int F, moep_dtype dt, float* logits,
+                          void* Y, void* ws, size_t ws_bytes, void* hip_stream, const char* who) {
   if (!valid_shape(T, E, H, F, dt, who)) return MOEP_EINVAL;
   if (int st = check_alignment(H, F, dt, who)) return st;
-  if (!Wgate || !W1 || !W3 || !W2) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
+  if (packed && dt != MOEP_BF16) return fail(MOEP_EUNSUPPORTED, "%s: packed weights exist for bf16 only", who);
+  if (!Wgate || (!packed && (!W1 || !W3 || !W2))) return fail(MOEP_EINVAL, "%s: NULL weight pointer", who);
   if (T == 0) return MOEP_OK;
   if (!x || !logits || !Y) return fail(MOEP_EINVAL, "%s: NULL x, logits or Y", who);
-  if (int st = check_ws(ws, ws_bytes, moe_expert_outputs_workspace(T, E, H, F, dt), who)) return st;
+  const size_t need = dt == MOEP_BF16 ? expert_outputs_workspace_bf16(T, E, H, F, packed != nullptr)
+                                      : moe_expert_outputs_workspace(T, E, H, F, dt);
+  if (int st = check_ws(ws, ws_bytes, need, who)) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t es = dtype_size(dt);
 
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   if (dt == MOEP_BF16) {
-    // Operands are packed once (x) or once per expert (weights) into the blocked layout of the packed
-    // GEMM; h stays in that layout between the two projections and never exists row-major.
+    // Operands are packed once per call into the blocked layout of the packed GEMM (x; every expert's
+    // weights, unless the caller has done that already); h stays in that layout between the two projections
+    // and never exists row-major.  Each projection is ONE launch over a batch of experts.
+    const int eb = experts_per_launch(T, E, F);
+    const size_t h_bytes = packed_a_bytes(T, F);
     char* hp = (char*)ws;
-    char* xp = hp + align256(packed_a_bytes(T, F));
-    char* wgu = xp + align256(packed_a_bytes(T, H));
-    char* wdn = wgu + align256(packed_b_bytes(F, H, true));
+    char* xp = hp + align256((size_t)eb * h_bytes);
+    const char* wgu = xp + align256(packed_a_bytes(T, H));
+    const char* wdn = wgu + align256((size_t)E * packed_b_bytes(F, H, true));
     if (int st = launch_pack_a_bf16(x, H, T, H, xp, s, "pack_x")) return st;
-    for (int e = 0; e < E; ++e) {
-      if (int st = launch_pack_b_bf16((const char*)W1 + (size_t)e * F * H * es, (const char*)W3 + (size_t)e * F * H * es,
-                                      F, H, 1, wgu, s, "pack_w")) return st;
-      if (int st = launch_pack_b_bf16((const char*)W2 + (size_t)e * H * F * es, nullptr, H, F, 1, wdn, s, "pack_w")) return st;
-      PackedGemmArgs up;                          // h = silu(x W1[e]^T) * (x W3[e]^T)
-      up.A = xp; up.B = wgu; up.C = hp;
+    if (packed) {                     // all W1/W3 pairs, then all W2
+      wgu = (const char*)packed;
+      wdn = wgu + (size_t)E * packed_b_bytes(F, H, true);
+    } else {
+      if (int st = launch_pack_b_bf16(W1, W3, F, H, E, (void*)wgu, s, "pack_w")) return st;
+      if (int st = launch_pack_b_bf16(W2, nullptr, H, F, E, (void*)wdn, s, "pack_w")) return st;
+    }
+    for (int e0 = 0; e0 < E; e0 += eb) {
+      const int ne = E - e0 < eb ? E - e0 : eb;
+      PackedGemmArgs up;                          // h[e] = silu(x W1[e]^T) * (x W3[e]^T)
+      up.A = xp; up.B = wgu + (size_t)e0 * packed_b_bytes(F, H, true); up.C = hp;
       up.M = T; up.N = F; up.K = H; up.epilogue = EPI_SWIGLU;
+      up.experts = ne; up.a_expert_bytes = 0; up.c_expert_bytes = (int64_t)h_bytes;
       if (int st = launch_gemm_bf16_packed(up, s, "gemm_gate_up_swiglu")) return st;
-      PackedGemmArgs down;                        // Y[e] = h W2[e]^T
-      down.A = hp; down.B = wdn; down.C = (char*)Y + (size_t)e * T * H * es; down.ldc = H;
+      PackedGemmArgs down;                        // Y[e] = h[e] W2[e]^T
+      down.A = hp; down.B = wdn + (size_t)e0 * packed_b_bytes(H, F, false);
+      down.C = (char*)Y + (size_t)e0 * T * H * es; down.ldc = H;
       down.M = T; down.N = H; down.K = F; down.epilogue = EPI_STORE;
+      down.experts = ne; down.a_expert_bytes = (int64_t)h_bytes; down.c_expert_bytes = (int64_t)((size_t)T * H * es);
       if (int st = launch_gemm_bf16_packed(down, s, "gemm_down")) return st;
     }
     return MOEP_OK;
@@ -249,6 +311,21 @@ int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const v
     if (int st = launch_gemm_f32(down, s, "gemm_down")) return st;
   }
   return MOEP_OK;
+}
+
+int moe_expert_outputs(const void* x, const void* Wgate, const void* W1, const void* W3,
+                       const void* W2, int64_t T, int E, int H, int F, moep_dtype dt,
+                       float* logits, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
+  return expert_outputs(x, Wgate, W1, W3, W2, nullptr, T, E, H, F, dt, logits, Y, ws, ws_bytes, hip_stream,
+                        "moe_expert_outputs");
+}
+
+int moe_expert_outputs_packed(const void* x, const void* Wgate, const void* packed_weights, int64_t T, int E,
+                              int H, int F, moep_dtype dt, float* logits, void* Y, void* ws, size_t ws_bytes,
+                              void* hip_stream) {
+  if (!packed_weights) return fail(MOEP_EINVAL, "moe_expert_outputs_packed: packed_weights is NULL");
+  return expert_outputs(x, Wgate, nullptr, nullptr, nullptr, packed_weights, T, E, H, F, dt, logits, Y, ws,
+                        ws_bytes, hip_stream, "moe_expert_outputs_packed");
 }
 
 // ------------------------------------------------------------------ prune_enumerate

@@ -86,6 +86,10 @@ struct PackedGemmArgs {
   const int32_t* seg_end = nullptr;
   const int32_t* tiles_in_use = nullptr;
   int64_t max_m_tiles = 0;
+  // Dense batched mode: `experts` GEMMs of the same shape in one launch; expert e reads A + e a_expert_bytes
+  // (0: every expert reads the same A), B + e packed_b_bytes(..), and writes C + e c_expert_bytes.
+  int experts = 1;
+  int64_t a_expert_bytes = 0, c_expert_bytes = 0;
 };
 size_t packed_a_bytes(int64_t rows, int K);
 size_t packed_b_bytes(int N, int K, bool gate_up_pair);

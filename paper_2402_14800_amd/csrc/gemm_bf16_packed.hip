@@ -45,6 +45,8 @@
 // Workgroup order: logical tile ids are dealt round-robin to the 8 XCDs (as the hardware deals
 // workgroups) and remapped so that every XCD works on a contiguous run of tiles, GROUP_M M-tiles deep
 // before moving along N, so that the 32 tiles in flight on one XCD share operand panels in its L2.
+#include <mutex>
+
 #include "common.h"
 
 namespace moep {
@@ -146,12 +148,18 @@ struct KArgs {
   const int32_t* tile_expert; const int32_t* tile_row0; const int32_t* seg_end; const int32_t* tiles_in_use;
   int64_t b_expert_bytes;
   const float* row_scale;
+  // dense batched mode: `experts` independent GEMMs of the same shape in one launch, tile ids expert-major;
+  // expert e reads A + e a_expert_bytes (0: A shared), B + e b_expert_bytes, writes C + e c_expert_bytes
+  int experts;
+  int64_t a_expert_bytes, c_expert_bytes;
 };
 
 // Round counters of the persistent workgroups, one per XCD (64 bytes apart); see round_sync in the kernel.
-// They only ever grow, by a multiple of the XCD's workgroup count per launch.  Launches that overlap on
-// one GPU share them: their workgroups may then wait for each other up to the bound, nothing else.
-__device__ unsigned int g_round_count[8 * 16];
+// They only ever grow, by a multiple of the XCD's workgroup count per launch; 64 bits wide, so they never wrap.
+// Launches that overlap on one GPU share them: their workgroups may then wait for each other up to the
+// bound, nothing else.  Workgroup b is taken to run on XCD b % 8 (how this part deals workgroups out); were
+// that ever not so, the line-ups would group the wrong workgroups and cost time, never a result.
+__device__ unsigned long long g_round_count[8 * 8];
 
 template <int EPI, bool GROUPED>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
@@ -165,22 +173,36 @@ void gemm_packed_kernel(KArgs p) {
   const int nsl = p.nsl;
   // Grouped launches are sized for the largest possible tile map; only its leading entries hold work.
   const uint32_t m_tiles = GROUPED ? (uint32_t)*p.tiles_in_use : (uint32_t)p.m_tiles;
-  const uint32_t nblk = m_tiles * (uint32_t)p.n_tiles;
+  const uint32_t per_expert = m_tiles * (uint32_t)p.n_tiles;
+  const uint32_t nblk = GROUPED ? per_expert : per_expert * (uint32_t)p.experts;
   const uint32_t G = gridDim.x;
 
   // Logical tile id -> (tm, tn).  Ids i, i + 8, ... belong to XCD i % 8 (the grid is a multiple of 8 or
   // a single round); every XCD gets a contiguous run of tiles, GROUP_M M-tiles deep.
   constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;   // measured: the long-K down projection prefers 4 x 8 tiles per XCD
   // weight blocks of the tile's expert
-  auto b_tile = [&](int tm_, int tn_) {
+  auto b_tile = [&](int tm_, int tn_, int e_) {
     const char* b = p.B + ((size_t)tn_ * nsl) * SLICE + wave_u * 4096;
-    if (GROUPED) b += (int64_t)p.tile_expert[tm_] * p.b_expert_bytes;
+    b += (int64_t)(GROUPED ? p.tile_expert[tm_] : e_) * p.b_expert_bytes;
     return b;
   };
-  auto decode = [&](uint32_t L, int& tm, int& tn) {
-    const uint32_t per = nblk >> 3, rem = nblk & 7;
+  // (e: the GEMM of a dense batched launch the tile belongs to; each of them is dealt to the XCDs exactly as
+  // a launch of its own would be when its tile count is a multiple of 8, else the batch is one flat run of tiles)
+  auto decode = [&](uint32_t L, int& tm, int& tn, int& e) {
     const uint32_t xcd = L & 7, j = L >> 3;
-    const uint32_t bid = xcd * per + (xcd < rem ? xcd : rem) + j;
+    uint32_t bid;
+    if (!GROUPED && (per_expert & 7) == 0) {
+      const uint32_t per8 = per_expert >> 3;
+      const uint32_t eu = j / per8;
+      e = (int)eu;
+      bid = xcd * per8 + (j - eu * per8);
+    } else {
+      const uint32_t per = nblk >> 3, rem = nblk & 7;
+      bid = xcd * per + (xcd < rem ? xcd : rem) + j;
+      const uint32_t eu = GROUPED ? 0u : bid / per_expert;
+      e = (int)eu;
+      bid -= eu * per_expert;
+    }
     const uint32_t group_sz = GROUP_M * (uint32_t)p.n_tiles;
     const uint32_t group = bid / group_sz;
     const uint32_t first_m = group * GROUP_M;
@@ -194,10 +216,10 @@ void gemm_packed_kernel(KArgs p) {
   // A wavefront moves 4 KB of each operand block per slice: KB 4 w .. 4 w + 3.
   uint32_t L_ld = blockIdx.x;
   if (L_ld >= nblk) return;
-  int tm_ld, tn_ld;
-  decode(L_ld, tm_ld, tn_ld);
-  const char* a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096;
-  const char* b_ld = b_tile(tm_ld, tn_ld);
+  int tm_ld, tn_ld, e_ld;
+  decode(L_ld, tm_ld, tn_ld, e_ld);
+  const char* a_ld = p.A + (int64_t)e_ld * p.a_expert_bytes + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096;
+  const char* b_ld = b_tile(tm_ld, tn_ld, e_ld);
   int s_ld = 0;
   int st_ld = 0;                      // byte offset of the stage the next slice goes to
   bool ld_ok = true;
@@ -233,27 +255,35 @@ void gemm_packed_kernel(KArgs p) {
   // apart); a workgroup that ran into the bound goes on alone and polls no more in this launch.  Only the
   // timing depends on any of this, never a result.
   const uint32_t rounds = (nblk + G - 1) / G;
-  const bool sync_on = nblk > G && (G & 7) == 0;
+  const bool sync_on = nblk > G && (G & 7) == 0 && (G >> 3) < 65536u;
   bool poll_ok = true;
   uint32_t switches = 0, arrivals = 0;
   const uint32_t arrivals_due = (rounds + SYNC_EVERY - 1) / SYNC_EVERY;
   auto round_sync = [&](bool last) {
-    if (wave_u != 0) return;
-    unsigned int* c = &g_round_count[(blockIdx.x & 7) * 16];
-    unsigned int old_v = 0;
+    int w_ = wave_u;                          // (opaque: the comparison is then made here, from a scalar register,
+    asm volatile("" : "+s"(w_));              // instead of being kept as a 0/1 value in a vector register across the K loop)
+    if (w_ != 0) return;
+    unsigned long long* c = &g_round_count[(blockIdx.x & 7) * 8];
+    unsigned long long old_v = 0;
     if (lane == 0)
-      old_v = __hip_atomic_fetch_add(c, last ? arrivals_due - arrivals : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      old_v = __hip_atomic_fetch_add(c, (unsigned long long)(last ? arrivals_due - arrivals : 1u), __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
     ++arrivals;
     if (last || !poll_ok) return;
-    // (wave-uniform arithmetic: keeps the division's constants in scalar registers)
-    const unsigned int n = G >> 3;
-    const unsigned int target = ((unsigned int)__builtin_amdgcn_readfirstlane((int)old_v) / n + 1) * n;
-    int polls = 0;
+    // Everyone has arrived when the count reaches the next multiple of n above the value this arrival saw.
+    // (wave-uniform 32-bit arithmetic: old mod n from the two halves of the 64-bit count, n < 2^16)
+    const uint32_t n = G >> 3;
+    const uint32_t old_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old_v);
+    const uint32_t old_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(old_v >> 32));
+    const uint32_t two32_mod_n = (0xffffffffu % n + 1u) % n;
+    const uint32_t old_mod_n = ((old_hi % n) * two32_mod_n + old_lo % n) % n;
+    const uint32_t target_lo = old_lo - old_mod_n + n;          // low word of the target; the count moves by far
+    int polls = 0;                                              // less than 2^31 while this workgroup waits
     for (;;) {
-      unsigned int now_v = 0;
-      if (lane == 0) now_v = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const unsigned int now = (unsigned int)__builtin_amdgcn_readfirstlane((int)now_v);
-      if ((int)(now - target) >= 0) break;
+      uint32_t now_v = 0;
+      if (lane == 0) now_v = (uint32_t)__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t now = (uint32_t)__builtin_amdgcn_readfirstlane((int)now_v);
+      if ((int32_t)(now - target_lo) >= 0) break;
       if (++polls >= SYNC_POLLS) { poll_ok = false; break; }
       __builtin_amdgcn_s_sleep(16);
     }
@@ -269,9 +299,9 @@ void gemm_packed_kernel(KArgs p) {
       __builtin_amdgcn_s_barrier();                                                             \
     }                                                                                           \
     if (L_ld < nblk) {                                                                          \
-      decode(L_ld, tm_ld, tn_ld);                                                               \
-      a_ld = p.A + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096;                               \
-      b_ld = b_tile(tm_ld, tn_ld);                                                              \
+      decode(L_ld, tm_ld, tn_ld, e_ld);                                                         \
+      a_ld = p.A + (int64_t)e_ld * p.a_expert_bytes + ((size_t)tm_ld * nsl) * SLICE + wave_u * 4096; \
+      b_ld = b_tile(tm_ld, tn_ld, e_ld);                                                        \
     } else {                                                                                    \
       ld_ok = false;                                                                            \
       a_ld -= SLICE; b_ld -= SLICE;                                                             \
@@ -376,8 +406,8 @@ void gemm_packed_kernel(KArgs p) {
   __builtin_amdgcn_sched_barrier(0);
 
   uint32_t L_mm = blockIdx.x;
-  int tm, tn;
-  decode(L_mm, tm, tn);
+  int tm, tn, e_mm;
+  decode(L_mm, tm, tn, e_mm);
   for (;;) {
     MOEP_ZERO_ACC()
     // The loader is NS - 1 slices ahead and changes tile between two runs of steps, never inside one.  K / 32
@@ -397,14 +427,17 @@ void gemm_packed_kernel(KArgs p) {
     // Register v of lane l of accumulator tile (i, j) holds output row 16 i + (l % 16) of the wavefront's
     // 128 rows and fragment row f = 4 (l / 16) + v of weight tile j; with the row permutation of the weight
     // blocks, tiles 2 P and 2 P + 1 together give the lane the 8 consecutive columns 32 P + 8 (l / 16) .. + 7.
-    int lane_e = lane;                        // opaque copy: keeps the epilogue's address arithmetic from being
-    asm volatile("" : "+v"(lane_e));          // hoisted above the K loop, where it would cost registers
+    // The lane id is recomputed here, in a form the compiler cannot move: anything derived from a value that
+    // lives across the K loop is hoisted above it and held (or spilled) there, and the loop has no register to spare.
+    int lane_e;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
     const int q8 = 8 * (lane_e >> 4);
     int64_t row0 = (int64_t)tm * 256, row_end = p.M;
     if (GROUPED) {
       row0 = p.tile_row0[tm];
       row_end = p.seg_end[p.tile_expert[tm]];
     }
+    char* const c_base = (char*)p.C + (GROUPED ? (int64_t)0 : (int64_t)e_mm * p.c_expert_bytes);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int prow = wm * 128 + i * 16 + (lane_e & 15);          // row inside the tile
@@ -428,7 +461,7 @@ void gemm_packed_kernel(KArgs p) {
             o[c] = __builtin_convertvector(h, bf16x2);
           }
           // packed A operand with K = N: slice n / 32, chunk (l / 16) of row prow
-          char* dst = (char*)p.C + ((size_t)tm * (p.N >> 5) + (n >> 5)) * SLICE + prow * 64 +
+          char* dst = c_base + ((size_t)tm * (p.N >> 5) + (n >> 5)) * SLICE + prow * 64 +
                       (((lane_e >> 4) ^ ((prow >> 2) & 3)) << 4);
           *(u32x4*)dst = __builtin_bit_cast(u32x4, o);
         }
@@ -445,10 +478,10 @@ void gemm_packed_kernel(KArgs p) {
               const f32x2 h = {acc[i][2 * P + (c >> 1)][2 * (c & 1)], acc[i][2 * P + (c >> 1)][2 * (c & 1) + 1]};
               o[c] = __builtin_convertvector(h, bf16x2);
             }
-            *(u32x4*)((uint16_t*)p.C + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
+            *(u32x4*)((uint16_t*)c_base + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
           } else {                                               // EPI_ROWSCALE_F32
             const float sc = p.row_scale[r];
-            float* dst = (float*)p.C + r * p.ldc + n;
+            float* dst = (float*)c_base + r * p.ldc + n;
             *(f32x4*)dst = sc * acc[i][2 * P];
             *(f32x4*)(dst + 4) = sc * acc[i][2 * P + 1];
           }
@@ -458,7 +491,7 @@ void gemm_packed_kernel(KArgs p) {
     }
     L_mm += G;
     if (L_mm >= nblk) break;   // (the loads still in flight are re-reads; the wavefront ends when they are back)
-    decode(L_mm, tm, tn);
+    decode(L_mm, tm, tn, e_mm);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);   // the re-reads still in flight target this workgroup's LDS
 #undef MOEP_LOAD1
@@ -474,28 +507,38 @@ void gemm_packed_kernel(KArgs p) {
 #undef MOEP_STEP
 }
 
-int compute_units() {
-  static int n = 0;
-  if (!n) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      return 256;
-    n = v;
-  }
-  return n;
-}
+// Per-device launch state, filled on a device's first launch under a mutex (first calls from several host
+// threads are safe): the compute-unit count, and whether each instantiation's dynamic LDS limit has been raised.
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+  int compute_units = 0;
+  bool attr_set[3][2] = {};
+};
+std::mutex g_dev_mu;
+DeviceState g_dev[kMaxDevices];
 
 template <int EPI, bool GROUPED>
 int launch(const KArgs& k, hipStream_t s) {
-  static bool attr_set = false;   // raising the dynamic LDS limit is per function, once
-  if (!attr_set) {
-    MOEP_HIP(hipFuncSetAttribute((const void*)gemm_packed_kernel<EPI, GROUPED>,
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-    attr_set = true;
+  int dev = 0, cus = 0;
+  MOEP_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MOEP_EUNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxDevices - 1);
+  {
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    DeviceState& d = g_dev[dev];
+    if (!d.compute_units) {
+      int v = 0;
+      MOEP_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+      d.compute_units = v > 0 ? v : 256;
+    }
+    if (!d.attr_set[EPI][GROUPED]) {   // raising the dynamic LDS limit is per function and device, once
+      MOEP_HIP(hipFuncSetAttribute((const void*)gemm_packed_kernel<EPI, GROUPED>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+      d.attr_set[EPI][GROUPED] = true;
+    }
+    cus = d.compute_units;
   }
-  const int64_t nblk = (int64_t)k.m_tiles * k.n_tiles;
-  int grid = compute_units() & ~7;            // one persistent workgroup per compute unit, a multiple of 8
+  const int64_t nblk = (int64_t)k.m_tiles * k.n_tiles * k.experts;
+  int grid = cus & ~7;                        // one persistent workgroup per compute unit, a multiple of 8
   if (grid < 8) grid = 8;
   if (nblk < grid) grid = (int)nblk;          // a single round: any size
   hipLaunchKernelGGL((gemm_packed_kernel<EPI, GROUPED>), dim3(grid), dim3(THREADS), LDS_BYTES, s, k);
@@ -571,9 +614,12 @@ int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* 
   k.tile_expert = g.tile_expert; k.tile_row0 = g.tile_row0; k.seg_end = g.seg_end; k.tiles_in_use = g.tiles_in_use;
   k.b_expert_bytes = (int64_t)packed_b_bytes(g.N, g.K, g.epilogue == EPI_SWIGLU);
   k.row_scale = g.row_scale;
+  if (g.experts < 1 || (grouped && g.experts != 1)) return fail(MOEP_EINVAL, "%s: bad batch count %d", name, g.experts);
+  k.experts = g.experts; k.a_expert_bytes = g.a_expert_bytes; k.c_expert_bytes = g.c_expert_bytes;
+  if ((g.a_expert_bytes | g.c_expert_bytes) & 15) return fail(MOEP_EUNSUPPORTED, "%s: per-expert strides must be multiples of 16 bytes", name);
   const int64_t m_tiles = grouped ? g.max_m_tiles : ceil_div(g.M, 256);
   const int64_t n_tiles = ceil_div(g.N, g.epilogue == EPI_SWIGLU ? 128 : 256);
-  if (m_tiles * n_tiles >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "%s: too many tiles", name);
+  if (m_tiles * n_tiles * g.experts >= ((int64_t)1 << 31)) return fail(MOEP_EUNSUPPORTED, "%s: too many tiles", name);
   k.m_tiles = (int)m_tiles; k.n_tiles = (int)n_tiles;
   Timed t(name, s);
   if (grouped) {

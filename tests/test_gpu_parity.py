@@ -219,6 +219,30 @@ def test_moe_expert_outputs_random_shapes(E, H, F, T):
     check_outputs(wl.to_f64(Y_t), ref_Y, "Y")
 
 
+def test_expert_pass_in_batches_of_experts_and_on_prepacked_weights():
+    """A layer whose intermediate activations exceed what one launch may hold (12 GiB): the 8 experts go through
+    the projections in batches of 3, 3 and 2.  One token of every M tile against the oracle, and the same call on
+    weights packed once gives the same bits."""
+    E, H, F, T = 8, 64, 14336, 131072 + 300
+    cfg, layer = small_layer("bf16", E, 2, H, F, 1, index=23)
+    cfg = cfg.with_tokens(T)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(cfg.seed)
+    d = to_dev(layer)
+    d["x"] = torch.randn((T, H), generator=gen, device=DEV).to(torch.bfloat16)
+    need = pkg.binding.moe_expert_outputs_workspace(T, E, H, F, 1)
+    per_expert_h = -(-T // 256) * 256 * F * 2
+    assert 3 * per_expert_h <= (12 << 30) < 4 * per_expert_h and need > 3 * per_expert_h
+    logits_t, Y_t = pkg.moe_expert_outputs(d["x"], d["Wgate"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    layer_x = dict(layer, x=d["x"])
+    sampled_expert_check(layer_x, logits_t, Y_t, torch.tensor(one_token_per_tile(T), device=DEV), weights_f64(layer))
+    packed = pkg.moe_pack_weights(d["W1"], d["W3"], d["W2"])
+    logits_p, Y_p = pkg.moe_expert_outputs_packed(d["x"], d["Wgate"], packed, F)
+    torch.cuda.synchronize()
+    assert torch.equal(logits_p, logits_t) and torch.equal(Y_p.view(torch.int16), Y_t.view(torch.int16))
+
+
 def test_config1_end_to_end():
     cfg = wl.CONFIGS["C1"]
     layer = wl.make_layer(cfg, device="cpu")

@@ -59,12 +59,18 @@ def test_subset_helpers_reject_bad_arguments():
 
 def test_workspace_queries_are_pure_host_arithmetic():
     assert binding.moe_expert_outputs_workspace(512, 4, 64, 128, binding.MOEP_F32) == 512 * 128 * 4
-    # bf16: h and x in the packed operand layout (rows padded to 256) plus one expert's packed W1/W3 pair and W2
+    # bf16: h of every expert of a launch and x in the packed operand layout (rows padded to 256) plus every
+    # expert's packed W1/W3 pair and W2
     T, H, F = 16384, 1024, 3584
     assert binding.moe_expert_outputs_workspace(T, 8, H, F, binding.MOEP_BF16) == (
-        T * F * 2 + T * H * 2 + (F // 128) * 256 * H * 2 + (H // 256) * 256 * F * 2)
+        8 * T * F * 2 + T * H * 2 + 8 * ((F // 128) * 256 * H * 2 + (H // 256) * 256 * F * 2))
     assert binding.moe_expert_outputs_workspace(300, 8, 64, 192, binding.MOEP_BF16) == (
-        512 * 192 * 2 + 512 * 64 * 2 + 2 * 256 * 64 * 2 + 1 * 256 * 192 * 2)
+        8 * 512 * 192 * 2 + 512 * 64 * 2 + 8 * (2 * 256 * 64 * 2 + 1 * 256 * 192 * 2))
+    # beyond 12 GiB of h the experts are taken in batches: the Mixtral-shaped layer goes one expert per launch
+    T3, H3, F3 = 262144, 4096, 14336
+    assert binding.moe_expert_outputs_workspace(T3, 8, H3, F3, binding.MOEP_BF16) == (
+        T3 * F3 * 2 + T3 * H3 * 2 + 8 * 3 * H3 * F3 * 2)
+    assert binding._lib.moe_expert_outputs_packed_workspace(T3, 8, H3, F3, binding.MOEP_BF16) == T3 * F3 * 2 + T3 * H3 * 2
     w6 = binding.prune_enumerate_workspace(16384, 8, 1024, 2, 6, binding.MOEP_BF16)
     w4 = binding.prune_enumerate_workspace(16384, 8, 1024, 2, 4, binding.MOEP_BF16)
     assert w6 >= 16384 * 64 * 4 and w4 > w6
