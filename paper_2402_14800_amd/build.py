@@ -28,9 +28,16 @@ FLAGS = [
 ]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+# Host-side sanitizers for the CPU test of the host logic (device code is compiled as usual): every -fsanitize=
+# goes to the host compilation only.
+SANITIZE_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                  "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+LIB_SANITIZED = os.path.join(OBJ, "sanitized", "libmoeprune_hostsan.so")
+
+
+def _compile(src: str, sanitize: bool = False) -> str:
+    obj = os.path.join(OBJ, "sanitized" if sanitize else "", src.replace(".hip", ".o"))
+    cmd = [HIPCC, *FLAGS, *(SANITIZE_FLAGS if sanitize else []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
@@ -40,15 +47,22 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 6) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(jobs: int = 6, sanitize: bool = False) -> str:
+    """Compiles every source and links the library.  sanitize=True builds a second library,
+    _build/sanitized/libmoeprune_hostsan.so, whose HOST code runs under AddressSanitizer and
+    UndefinedBehaviorSanitizer (for the CPU tests of subset indexing, workspace planning and argument checks;
+    a program that loads it must itself be linked with the sanitizer runtime)."""
+    os.makedirs(os.path.join(OBJ, "sanitized") if sanitize else OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        objs = list(pool.map(lambda src: _compile(src, sanitize), SOURCES))
+    lib = LIB_SANITIZED if sanitize else LIB
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
+    if sanitize:
+        cmd += ["-fsanitize=address,undefined", "-fno-gpu-sanitize", "-shared-libsan"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    return LIB
+    return lib
 
 
 def kernel_resource_usage(src: str) -> dict:

@@ -446,6 +446,11 @@ __global__ __launch_bounds__(1024) void argmin_kernel(const float* __restrict__ 
   }
 }
 
+// Lanes per scoring workgroup: one lane per subset, whole wavefronts, at most four of them.
+int score_threads(int64_t n_sub) {
+  return n_sub >= 256 ? 256 : (int)((n_sub + 63) / 64) * 64;
+}
+
 int capacity_for(int n_act) {
   const int caps[] = {2, 4, 6, 8, 12, 16, 32};
   for (int c : caps)
@@ -468,7 +473,7 @@ int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
   const int cap = capacity_for(p->n_act);
   p->rec_floats = rec_size(cap);
   // Aim for a few thousand scoring workgroups; tiles of 32..256 tokens.
-  const int64_t sub_blocks = ceil_div(p->n_sub, p->n_sub <= 64 ? 64 : 256);
+  const int64_t sub_blocks = ceil_div(p->n_sub, score_threads(p->n_sub));
   int tile = 256;
   while (tile > 32 && sub_blocks * ceil_div(T, tile) < 4096) tile >>= 1;
   p->tok_tile = tile;
@@ -487,7 +492,7 @@ int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
 template <int CAP>
 static void launch_score(const EnumPlan& p, const float* rec, float* partial, uint32_t* pcnt,
                          hipStream_t s) {
-  const int threads = p.n_sub <= 64 ? 64 : 256;
+  const int threads = score_threads(p.n_sub);
   dim3 grid((unsigned)ceil_div(p.n_sub, threads), (unsigned)p.n_tok_tiles);
   if (p.n_act == CAP)
     hipLaunchKernelGGL((score_kernel<CAP, true>), grid, dim3(threads), 0, s, rec, p.T, p.tok_tile, p.E, p.r,
