@@ -398,9 +398,10 @@ int prune_enumerate_multi(const float* logits, const void* Y, int64_t T, int E, 
 // by expert) goes through its expert, and the down projection scales it by the slot's routing weight.
 // With `plain_out` the down projection instead stores the unscaled expert output of every slot there,
 // in the storage dtype.
+// `direct_out` (bf16 path, row-scaled mode): the layer output; slots that are a token's only one are written there.
 static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, const void* W3,
                           const void* W2, moep_dtype dt, char* w, hipStream_t s, void* plain_out = nullptr,
-                          const void* packed = nullptr) {
+                          const void* packed = nullptr, void* direct_out = nullptr) {
   const int H = p.H, F = p.F;
   if (dt == MOEP_BF16) {
     // Packed-operand path: the routed rows of x are gathered into one 256-row block per tile, every
@@ -433,6 +434,10 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
     down.N = H; down.K = F;
     down.epilogue = plain_out ? EPI_STORE : EPI_ROWSCALE_F32;
     down.row_scale = plain_out ? nullptr : (const float*)(w + p.off_slot_scale);
+    if (!plain_out && direct_out) {
+      down.row_dest = (const int32_t*)(w + p.off_slot_dest);
+      down.direct_out = direct_out;
+    }
     return launch_gemm_bf16_packed(down, s, "gemm_down_routed");
   }
   GemmArgs up;                      // h[slot] = silu(x[token(slot)] W1[e]^T) * (x[..] W3[e]^T)
@@ -506,9 +511,11 @@ static int forward_pruned_skip(const void* x, const void* Wgate, const void* W1,
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   if (int st = launch_skip_routing(p, logits, kept_mask, beta, skip_mask, top2_out, w, s)) return st;
 
-  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s, nullptr, packed)) return st;
+  // bf16: the down projection writes the output of every token routed to a single expert itself
+  void* direct = dt == MOEP_BF16 ? out : nullptr;
+  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s, nullptr, packed, direct)) return st;
   (void)es;
-  return launch_skip_combine(p, dt, skip_mask, out, w, s);
+  return launch_skip_combine(p, dt, skip_mask, out, w, s, direct != nullptr);
 }
 
 int moe_forward_pruned_skip(const void* x, const void* Wgate, const void* W1, const void* W3,
@@ -585,8 +592,9 @@ int moe_forward_skip_topk(const void* x, const void* Wgate, const void* W1, cons
   float* logits = logits_out ? logits_out : (float*)(w + p.off_logits);
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   if (int st = launch_skip_topk_routing(p, logits, kept_mask, beta, n_used, topk_out, w, s)) return st;
-  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s)) return st;
-  return launch_skip_topk_combine(p, dt, out, w, s);
+  void* direct = dt == MOEP_BF16 ? out : nullptr;
+  if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s, nullptr, nullptr, direct)) return st;
+  return launch_skip_topk_combine(p, dt, out, w, s, direct != nullptr);
 }
 
 // ------------------------------------------------------------------ skip_calibrate_beta

@@ -90,6 +90,11 @@ struct PackedGemmArgs {
   // (0: every expert reads the same A), B + e packed_b_bytes(..), and writes C + e c_expert_bytes.
   int experts = 1;
   int64_t a_expert_bytes = 0, c_expert_bytes = 0;
+  // EPI_ROWSCALE_F32, optional: rows r with row_dest[r] >= 0 are not written to C but, rounded to bf16 and
+  // unscaled (their scale is 1), to row row_dest[r] of `direct_out` (leading dimension ldc): the slots of
+  // tokens that were routed to a single expert go straight to the layer output.
+  const int32_t* row_dest = nullptr;
+  void* direct_out = nullptr;
 };
 size_t packed_a_bytes(int64_t rows, int K);
 size_t packed_b_bytes(int N, int K, bool gate_up_pair);
@@ -138,18 +143,19 @@ struct SkipPlan {
   int ks;                // slots per token (2 for the top-2 rule, k for the generalised rule)
   int64_t max_slots;     // ks T
   int64_t max_tiles;     // upper bound on M tiles over all experts
-  size_t off_logits, off_slot_token, off_slot_scale, off_pos, off_counts, off_seg_end,
+  size_t off_logits, off_slot_token, off_slot_scale, off_slot_dest, off_pos, off_counts, off_seg_end,
          off_tile_expert, off_tile_row0, off_h, off_xp, off_w13, off_w2, off_slot_out, total;
 };
 int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p, bool with_slot_out = true);
 int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,
                         int32_t* top2_out, char* ws, hipStream_t s);
+// `singles_done`: tokens routed to a single expert already have their output (written by the down projection)
 int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
-                        char* ws, hipStream_t s);
+                        char* ws, hipStream_t s, bool singles_done);
 int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta,
                              int32_t* n_used, int32_t* topk_out, char* ws, hipStream_t s,
                              int32_t* pos_out = nullptr);
-int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s);
+int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s, bool singles_done);
 
 // ---- beta calibration -----------------------------------------------------------------
 size_t calibrate_workspace_bytes(int64_t T);

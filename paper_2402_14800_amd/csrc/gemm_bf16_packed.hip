@@ -152,6 +152,9 @@ struct KArgs {
   // expert e reads A + e a_expert_bytes (0: A shared), B + e b_expert_bytes, writes C + e c_expert_bytes
   int experts;
   int64_t a_expert_bytes, c_expert_bytes;
+  // EPI_ROWSCALE_F32: rows with row_dest[r] >= 0 go, as bf16 and unscaled, to row row_dest[r] of direct_out
+  const int32_t* row_dest;
+  uint16_t* direct_out;
 };
 
 // Round counters of the persistent workgroups, one per XCD (64 bytes apart); see round_sync in the kernel.
@@ -467,18 +470,21 @@ void gemm_packed_kernel(KArgs p) {
         }
         }
       } else {
+        int64_t dest = -1;                                       // EPI_ROWSCALE_F32: >= 0: this row is a token's only slot
+        if (EPI == EPI_ROWSCALE_F32 && p.row_dest) dest = p.row_dest[r];
 #pragma unroll
         for (int P = 0; P < 4; ++P) {
           const int n = tn * 256 + wn * 128 + 32 * P + q8;
           if (n >= p.N) continue;
-          if (EPI == EPI_STORE) {
+          if (EPI == EPI_STORE || (EPI == EPI_ROWSCALE_F32 && dest >= 0)) {
             bf16x2 o[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
               const f32x2 h = {acc[i][2 * P + (c >> 1)][2 * (c & 1)], acc[i][2 * P + (c >> 1)][2 * (c & 1) + 1]};
               o[c] = __builtin_convertvector(h, bf16x2);
             }
-            *(u32x4*)((uint16_t*)c_base + r * p.ldc + n) = __builtin_bit_cast(u32x4, o);
+            uint16_t* const row = EPI == EPI_STORE ? (uint16_t*)c_base + r * p.ldc : p.direct_out + dest * p.ldc;
+            *(u32x4*)(row + n) = __builtin_bit_cast(u32x4, o);
           } else {                                               // EPI_ROWSCALE_F32
             const float sc = p.row_scale[r];
             float* dst = (float*)c_base + r * p.ldc + n;
@@ -616,6 +622,9 @@ int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* 
   k.row_scale = g.row_scale;
   if (g.experts < 1 || (grouped && g.experts != 1)) return fail(MOEP_EINVAL, "%s: bad batch count %d", name, g.experts);
   k.experts = g.experts; k.a_expert_bytes = g.a_expert_bytes; k.c_expert_bytes = g.c_expert_bytes;
+  if (g.row_dest && (g.epilogue != EPI_ROWSCALE_F32 || !g.direct_out || ((uintptr_t)g.direct_out & 15)))
+    return fail(MOEP_EINVAL, "%s: row_dest needs the row-scaled epilogue and a 16-byte aligned direct_out", name);
+  k.row_dest = g.row_dest; k.direct_out = (uint16_t*)g.direct_out;
   if ((g.a_expert_bytes | g.c_expert_bytes) & 15) return fail(MOEP_EUNSUPPORTED, "%s: per-expert strides must be multiples of 16 bytes", name);
   const int64_t m_tiles = grouped ? g.max_m_tiles : ceil_div(g.M, 256);
   const int64_t n_tiles = ceil_div(g.N, g.epilogue == EPI_SWIGLU ? 128 : 256);

@@ -110,6 +110,7 @@ __global__ __launch_bounds__(RB) void scatter_kernel(const int32_t* __restrict__
                                                      const int32_t* __restrict__ base, int64_t T,
                                                      int E, int32_t* __restrict__ slot_token,
                                                      float* __restrict__ slot_scale,
+                                                     int32_t* __restrict__ slot_dest,
                                                      int32_t* __restrict__ pos) {
   __shared__ int wave_cnt[RB / 64][32];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -132,6 +133,7 @@ __global__ __launch_bounds__(RB) void scatter_kernel(const int32_t* __restrict__
   for (int w = 0; w < wave; ++w) p0 += wave_cnt[w][e0];
   slot_token[p0] = (int32_t)t;
   slot_scale[p0] = tw[2 * t];
+  slot_dest[p0] = e1 >= 0 ? -1 : (int32_t)t;      // a skipped token's only slot (weight 1) is the token's output
   pos[2 * t] = p0;
   int p1 = -1;
   if (e1 >= 0) {
@@ -139,6 +141,7 @@ __global__ __launch_bounds__(RB) void scatter_kernel(const int32_t* __restrict__
     for (int w = 0; w < wave; ++w) p1 += wave_cnt[w][e1];
     slot_token[p1] = (int32_t)t;
     slot_scale[p1] = tw[2 * t + 1];
+    slot_dest[p1] = -1;
   }
   pos[2 * t + 1] = p1;
 }
@@ -152,12 +155,13 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__ slot_out,
                                                       const int32_t* __restrict__ pos, int64_t T,
-                                                      int H4, void* __restrict__ out) {
+                                                      int H4, void* __restrict__ out, bool singles_done) {
   const int64_t n = T * H4;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const int64_t t = i / H4;
     const int c = (int)(i - t * H4);
     const int p0 = pos[2 * t], p1 = pos[2 * t + 1];
+    if (singles_done && p1 < 0) continue;       // written by the down projection
     float4 v = slot_out[(int64_t)p0 * H4 + c];
     if (p1 >= 0) {
       const float4 u = slot_out[(int64_t)p1 * H4 + c];
@@ -240,6 +244,7 @@ __global__ __launch_bounds__(RB) void scatter_topk_kernel(const int32_t* __restr
                                                           const int32_t* __restrict__ base, int64_t T,
                                                           int E, int32_t* __restrict__ slot_token,
                                                           float* __restrict__ slot_scale,
+                                                          int32_t* __restrict__ slot_dest,
                                                           int32_t* __restrict__ pos) {
   __shared__ int wave_cnt[RB / 64][32];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -271,6 +276,7 @@ __global__ __launch_bounds__(RB) void scatter_topk_kernel(const int32_t* __restr
       for (int w = 0; w < wave; ++w) p += wave_cnt[w][es[m]];
       slot_token[p] = (int32_t)t;
       slot_scale[p] = tw[t * K + m];
+      slot_dest[p] = nu == 1 ? (int32_t)t : -1;     // a token's only slot (weight 1) is the token's output
     }
     pos[t * K + m] = p;
   }
@@ -279,11 +285,12 @@ __global__ __launch_bounds__(RB) void scatter_topk_kernel(const int32_t* __restr
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_topk_kernel(const float4* __restrict__ slot_out,
                                                            const int32_t* __restrict__ pos, int64_t T,
-                                                           int H4, int K, void* __restrict__ out) {
+                                                           int H4, int K, void* __restrict__ out, bool singles_done) {
   const int64_t n = T * H4;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const int64_t t = i / H4;
     const int c = (int)(i - t * H4);
+    if (singles_done && (K == 1 || pos[t * K + 1] < 0)) continue;     // written by the down projection
     float4 v = slot_out[(int64_t)pos[t * K] * H4 + c];     // the best expert is always kept
     for (int m = 1; m < K; ++m) {
       const int p = pos[t * K + m];
@@ -315,6 +322,7 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p
   p->off_logits = take((size_t)T * E * 4);
   p->off_slot_token = take((size_t)p->max_slots * 4);
   p->off_slot_scale = take((size_t)p->max_slots * 4);
+  p->off_slot_dest = take((size_t)p->max_slots * 4);
   p->off_pos = take((size_t)T * ks * 4 * 3);           // pos, experts, weights: [T,ks] each
   p->off_counts = take((size_t)n_blocks * E * 4);
   p->off_seg_end = take((size_t)E * 4);
@@ -353,13 +361,13 @@ int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_ma
                      (int32_t*)(ws + p.off_tile_row0), (int)p.max_tiles);
   hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)n_blocks), dim3(RB), 0, s, top2, tw, skip_mask,
                      counts, T, p.E, (int32_t*)(ws + p.off_slot_token),
-                     (float*)(ws + p.off_slot_scale), pos);
+                     (float*)(ws + p.off_slot_scale), (int32_t*)(ws + p.off_slot_dest), pos);
   MOEP_HIP(hipGetLastError());
   return MOEP_OK;
 }
 
 int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_mask, void* out,
-                        char* ws, hipStream_t s) {
+                        char* ws, hipStream_t s, bool singles_done) {
   (void)skip_mask;
   const int H4 = p.H / 4;
   const int64_t n = p.T * H4;
@@ -367,10 +375,10 @@ int launch_skip_combine(const SkipPlan& p, moep_dtype dt, const uint8_t* skip_ma
   Timed t("skip_combine", s);
   if (dt == MOEP_BF16)
     hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(256), 0, s,
-                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out);
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out, singles_done);
   else
     hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(256), 0, s,
-                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out);
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, out, singles_done);
   MOEP_HIP(hipGetLastError());
   return MOEP_OK;
 }
@@ -388,6 +396,7 @@ int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t ke
   const int64_t n_blocks = ceil_div(T, RB);
   int32_t* slot_token = (int32_t*)(ws + p.off_slot_token);
   float* slot_scale = (float*)(ws + p.off_slot_scale);
+  int32_t* slot_dest = (int32_t*)(ws + p.off_slot_dest);
   Timed t("skip_route_dispatch", s);
 #define MOEP_ROUTE_CASE(KK)                                                                    \
   case KK:                                                                                    \
@@ -408,7 +417,7 @@ int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t ke
 #define MOEP_SCATTER_CASE(KK)                                                                  \
   case KK:                                                                                    \
     hipLaunchKernelGGL(scatter_topk_kernel<KK>, dim3((unsigned)n_blocks), dim3(RB), 0, s, topk, tw, \
-                       n_used, counts, T, p.E, slot_token, slot_scale, pos);                  \
+                       n_used, counts, T, p.E, slot_token, slot_scale, slot_dest, pos);       \
     break;
   switch (K) {
     MOEP_SCATTER_CASE(1) MOEP_SCATTER_CASE(2) MOEP_SCATTER_CASE(3) MOEP_SCATTER_CASE(4)
@@ -421,17 +430,17 @@ int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t ke
   return MOEP_OK;
 }
 
-int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s) {
+int launch_skip_topk_combine(const SkipPlan& p, moep_dtype dt, void* out, char* ws, hipStream_t s, bool singles_done) {
   const int H4 = p.H / 4;
   const int64_t n = p.T * H4;
   const unsigned blocks = (unsigned)(ceil_div(n, 256) < 65536 ? ceil_div(n, 256) : 65536);
   Timed t("skip_combine", s);
   if (dt == MOEP_BF16)
     hipLaunchKernelGGL(combine_topk_kernel<true>, dim3(blocks), dim3(256), 0, s,
-                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, p.ks, out);
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, p.ks, out, singles_done);
   else
     hipLaunchKernelGGL(combine_topk_kernel<false>, dim3(blocks), dim3(256), 0, s,
-                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, p.ks, out);
+                       (const float4*)(ws + p.off_slot_out), (const int32_t*)(ws + p.off_pos), p.T, H4, p.ks, out, singles_done);
   MOEP_HIP(hipGetLastError());
   return MOEP_OK;
 }
