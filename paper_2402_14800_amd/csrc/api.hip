@@ -427,8 +427,10 @@ static int run_routed_ffn(const SkipPlan& p, const void* x, const void* W1, cons
     up.M = p.max_slots; up.N = F; up.K = H; up.epilogue = EPI_SWIGLU;
     up.tile_expert = tile_expert; up.tile_row0 = tile_row0; up.seg_end = seg_end; up.tiles_in_use = tiles_in_use;
     up.max_m_tiles = p.max_tiles;
+    up.tile_order = (const uint32_t*)(w + p.off_order_up);
     if (int st = launch_gemm_bf16_packed(up, s, "gemm_gate_up_swiglu_routed")) return st;
     PackedGemmArgs down = up;
+    down.tile_order = (const uint32_t*)(w + p.off_order_down);
     down.A = w + p.off_h; down.B = w2;
     down.C = plain_out ? plain_out : w + p.off_slot_out; down.ldc = H;
     down.N = H; down.K = F;

@@ -65,6 +65,10 @@ struct GemmArgs {
 };
 
 constexpr int GEMM_BM = 256;   // rows per tile of either GEMM implementation's grouped map
+// bf16 packed GEMM: M tiles per group of tiles that an XCD works through together, and output columns per tile,
+// for the gate/up (SwiGLU) and the down projection (measured: the long-K down projection prefers 4 x 8 tiles per XCD)
+constexpr int GEMM_GROUP_M_SWIGLU = 8, GEMM_GROUP_M_STORE = 4;
+constexpr int GEMM_BN_SWIGLU = 128, GEMM_BN_STORE = 256;
 
 int launch_gemm_f32(const GemmArgs& g, hipStream_t s, const char* name);
 
@@ -86,6 +90,9 @@ struct PackedGemmArgs {
   const int32_t* seg_end = nullptr;
   const int32_t* tiles_in_use = nullptr;
   int64_t max_m_tiles = 0;
+  // Grouped mode, optional: the order in which the launch walks its tiles, entry i = (M tile << 12) | N tile,
+  // tiles_in_use x n_tiles entries (see order_kernel in skip.hip); without it groups of M tiles may straddle experts.
+  const uint32_t* tile_order = nullptr;
   // Dense batched mode: `experts` GEMMs of the same shape in one launch; expert e reads A + e a_expert_bytes
   // (0: every expert reads the same A), B + e packed_b_bytes(..), and writes C + e c_expert_bytes.
   int experts = 1;
@@ -144,7 +151,8 @@ struct SkipPlan {
   int64_t max_slots;     // ks T
   int64_t max_tiles;     // upper bound on M tiles over all experts
   size_t off_logits, off_slot_token, off_slot_scale, off_slot_dest, off_pos, off_counts, off_seg_end,
-         off_tile_expert, off_tile_row0, off_h, off_xp, off_w13, off_w2, off_slot_out, total;
+         off_tile_expert, off_tile_row0, off_order_up, off_order_down, off_h, off_xp, off_w13, off_w2, off_slot_out, total;
+  bool packed;           // bf16: packed-operand GEMMs (tile order tables are built)
 };
 int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p, bool with_slot_out = true);
 int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,

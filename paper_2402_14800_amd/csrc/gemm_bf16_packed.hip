@@ -45,6 +45,8 @@
 // Workgroup order: logical tile ids are dealt round-robin to the 8 XCDs (as the hardware deals
 // workgroups) and remapped so that every XCD works on a contiguous run of tiles, GROUP_M M-tiles deep
 // before moving along N, so that the 32 tiles in flight on one XCD share operand panels in its L2.
+// Grouped launches read that order from a table the dispatch kernels lay out, with the groups of M tiles
+// aligned to the experts' segments (a group that straddled two experts would share no weight panel).
 #include <mutex>
 
 #include "common.h"
@@ -155,6 +157,7 @@ struct KArgs {
   // EPI_ROWSCALE_F32: rows with row_dest[r] >= 0 go, as bf16 and unscaled, to row row_dest[r] of direct_out
   const int32_t* row_dest;
   uint16_t* direct_out;
+  const uint32_t* tile_order;   // grouped mode, optional: entry bid = (M tile << 12) | N tile
 };
 
 // Round counters of the persistent workgroups, one per XCD (64 bytes apart); see round_sync in the kernel.
@@ -182,37 +185,47 @@ void gemm_packed_kernel(KArgs p) {
 
   // Logical tile id -> (tm, tn).  Ids i, i + 8, ... belong to XCD i % 8 (the grid is a multiple of 8 or
   // a single round); every XCD gets a contiguous run of tiles, GROUP_M M-tiles deep.
-  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? 8 : 4;   // measured: the long-K down projection prefers 4 x 8 tiles per XCD
+  constexpr uint32_t GROUP_M = EPI == EPI_SWIGLU ? GEMM_GROUP_M_SWIGLU : GEMM_GROUP_M_STORE;
   // weight blocks of the tile's expert
   auto b_tile = [&](int tm_, int tn_, int e_) {
     const char* b = p.B + ((size_t)tn_ * nsl) * SLICE + wave_u * 4096;
     b += (int64_t)(GROUPED ? p.tile_expert[tm_] : e_) * p.b_expert_bytes;
     return b;
   };
-  // (e: the GEMM of a dense batched launch the tile belongs to; each of them is dealt to the XCDs exactly as
-  // a launch of its own would be when its tile count is a multiple of 8, else the batch is one flat run of tiles)
+  // Dense: e = the GEMM of a batched launch the tile belongs to; each of them is dealt to the XCDs exactly as a
+  // launch of its own would be when its tile count is a multiple of 8, else the batch is one flat run of tiles.
   auto decode = [&](uint32_t L, int& tm, int& tn, int& e) {
     const uint32_t xcd = L & 7, j = L >> 3;
-    uint32_t bid;
-    if (!GROUPED && (per_expert & 7) == 0) {
-      const uint32_t per8 = per_expert >> 3;
-      const uint32_t eu = j / per8;
-      e = (int)eu;
-      bid = xcd * per8 + (j - eu * per8);
-    } else {
+    if (GROUPED) {
+      // the order of the tiles was laid out by the caller (groups of M tiles aligned to experts, see order_kernel);
+      // XCD x walks entries x per + min(x, rem) ... of it
       const uint32_t per = nblk >> 3, rem = nblk & 7;
-      bid = xcd * per + (xcd < rem ? xcd : rem) + j;
-      const uint32_t eu = GROUPED ? 0u : bid / per_expert;
-      e = (int)eu;
-      bid -= eu * per_expert;
+      const uint32_t v = p.tile_order[xcd * per + (xcd < rem ? xcd : rem) + j];
+      e = 0;
+      tm = (int)(v >> 12);
+      tn = (int)(v & 4095u);
+    } else {
+      uint32_t bid;
+      if ((per_expert & 7) == 0) {
+        const uint32_t per8 = per_expert >> 3;
+        const uint32_t eu = j / per8;
+        e = (int)eu;
+        bid = xcd * per8 + (j - eu * per8);
+      } else {
+        const uint32_t per = nblk >> 3, rem = nblk & 7;
+        bid = xcd * per + (xcd < rem ? xcd : rem) + j;
+        const uint32_t eu = bid / per_expert;
+        e = (int)eu;
+        bid -= eu * per_expert;
+      }
+      const uint32_t group_sz = GROUP_M * (uint32_t)p.n_tiles;
+      const uint32_t group = bid / group_sz;
+      const uint32_t first_m = group * GROUP_M;
+      const uint32_t gm = min(m_tiles - first_m, GROUP_M);
+      const uint32_t in_group = bid - group * group_sz;
+      tm = (int)(first_m + in_group % gm);
+      tn = (int)(in_group / gm);
     }
-    const uint32_t group_sz = GROUP_M * (uint32_t)p.n_tiles;
-    const uint32_t group = bid / group_sz;
-    const uint32_t first_m = group * GROUP_M;
-    const uint32_t gm = min(m_tiles - first_m, GROUP_M);
-    const uint32_t in_group = bid - group * group_sz;
-    tm = (int)(first_m + in_group % gm);
-    tn = (int)(in_group / gm);
   };
 
   // ---- loader state (all wave-uniform) ----------------------------------------------------------
@@ -611,7 +624,7 @@ int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* 
     return fail(MOEP_EUNSUPPORTED, "%s: operands must be 16-byte aligned", name);
   if (g.epilogue != EPI_SWIGLU && (g.ldc % 8 || g.ldc < g.N)) return fail(MOEP_EINVAL, "%s: bad leading dimension", name);
   const bool grouped = g.tile_expert != nullptr;
-  if (grouped && (!g.tile_row0 || !g.seg_end || !g.tiles_in_use || g.max_m_tiles <= 0))
+  if (grouped && (!g.tile_row0 || !g.seg_end || !g.tiles_in_use || !g.tile_order || g.max_m_tiles <= 0))
     return fail(MOEP_EINVAL, "%s: incomplete tile map", name);
   if (g.epilogue == EPI_ROWSCALE_F32 && !g.row_scale) return fail(MOEP_EINVAL, "%s: row_scale is NULL", name);
   KArgs k = {};
@@ -625,6 +638,7 @@ int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* 
   if (g.row_dest && (g.epilogue != EPI_ROWSCALE_F32 || !g.direct_out || ((uintptr_t)g.direct_out & 15)))
     return fail(MOEP_EINVAL, "%s: row_dest needs the row-scaled epilogue and a 16-byte aligned direct_out", name);
   k.row_dest = g.row_dest; k.direct_out = (uint16_t*)g.direct_out;
+  k.tile_order = grouped ? g.tile_order : nullptr;
   if ((g.a_expert_bytes | g.c_expert_bytes) & 15) return fail(MOEP_EUNSUPPORTED, "%s: per-expert strides must be multiples of 16 bytes", name);
   const int64_t m_tiles = grouped ? g.max_m_tiles : ceil_div(g.M, 256);
   const int64_t n_tiles = ceil_div(g.N, g.epilogue == EPI_SWIGLU ? 128 : 256);

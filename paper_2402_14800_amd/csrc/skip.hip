@@ -61,6 +61,8 @@ __global__ __launch_bounds__(RB) void route_kernel(const float* __restrict__ log
   if ((int)threadIdx.x < E) counts[(int64_t)blockIdx.x * E + threadIdx.x] = cnt[threadIdx.x];
 }
 
+// seg_end holds 2 E + 1 ints: the E segment ends, then the index of each expert's first tile (E + 1 entries,
+// the last one being the number of tiles in use).
 __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ counts, int64_t n_blocks,
                                                    int E, int32_t* __restrict__ seg_end,
                                                    int32_t* __restrict__ tile_expert,
@@ -79,12 +81,15 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ counts,
     for (int i = 0; i < E; ++i) { begin[i] = run; run += total[i]; }
     begin[E] = run;
     int idx = 0;
-    for (int i = 0; i < E; ++i)
+    for (int i = 0; i < E; ++i) {
+      seg_end[E + i] = idx;
       for (int row = begin[i]; row < begin[i + 1] && idx < max_tiles; row += GEMM_BM) {
         tile_expert[idx] = i;
         tile_row0[idx] = row;
         ++idx;
       }
+    }
+    seg_end[2 * E] = idx;
     n_tiles = idx;
     tile_expert[max_tiles] = idx;          // number of tiles in use, read by the grouped GEMMs
   }
@@ -102,6 +107,31 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ counts,
     tile_expert[i] = -1;
     tile_row0[i] = 0;
   }
+}
+
+// The order in which a grouped GEMM launch walks its tiles.  The launch gives every XCD a contiguous run of this
+// list; within a run, 32 consecutive entries are in flight together and share operand panels through the XCD's L2.
+// Entries are grouped per EXPERT: group_m consecutive M tiles of one expert, walked along N (all group_m tiles of
+// one N tile, then the next N tile), so that the tiles in flight share the same few weight panels; an expert's last
+// group may be smaller.  Entry = (M tile << 12) | N tile.
+__global__ __launch_bounds__(256) void order_kernel(const int32_t* __restrict__ expert_first, int E, int n_tiles,
+                                                    int group_m, uint32_t* __restrict__ order) {
+  __shared__ int first[33];
+  if ((int)threadIdx.x <= E) first[threadIdx.x] = expert_first[threadIdx.x];
+  __syncthreads();
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (int64_t)first[E] * n_tiles) return;
+  int e = 0;
+  while (e + 1 < E && (int64_t)first[e + 1] * n_tiles <= q) ++e;
+  const int64_t qe = q - (int64_t)first[e] * n_tiles;
+  const int c = first[e + 1] - first[e];
+  const int64_t gsz = (int64_t)group_m * n_tiles;
+  const int g = (int)(qe / gsz);
+  const int first_m = g * group_m;
+  const int gm = c - first_m < group_m ? c - first_m : group_m;
+  const int in_group = (int)(qe - g * gsz);
+  const int tn = in_group / gm, m = first_m + in_group % gm;
+  order[q] = ((uint32_t)(first[e] + m) << 12) | (uint32_t)tn;
 }
 
 __global__ __launch_bounds__(RB) void scatter_kernel(const int32_t* __restrict__ top2,
@@ -325,10 +355,16 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p
   p->off_slot_dest = take((size_t)p->max_slots * 4);
   p->off_pos = take((size_t)T * ks * 4 * 3);           // pos, experts, weights: [T,ks] each
   p->off_counts = take((size_t)n_blocks * E * 4);
-  p->off_seg_end = take((size_t)E * 4);
+  p->off_seg_end = take((size_t)(2 * E + 1) * 4);          // segment ends, then each expert's first tile
   p->off_tile_expert = take((size_t)(p->max_tiles + 1) * 4);   // + the count of tiles in use
   p->off_tile_row0 = take((size_t)p->max_tiles * 4);
+  p->packed = dt == MOEP_BF16;
+  p->off_order_up = p->off_order_down = 0;
   if (dt == MOEP_BF16) {
+    if (ceil_div(F, GEMM_BN_SWIGLU) > 4096 || ceil_div(H, GEMM_BN_STORE) > 4096 || p->max_tiles >= (1 << 20))
+      return fail(MOEP_EUNSUPPORTED, "moe_forward_skip: too many tiles for the tile order tables");
+    p->off_order_up = take((size_t)p->max_tiles * ceil_div(F, GEMM_BN_SWIGLU) * 4);
+    p->off_order_down = take((size_t)p->max_tiles * ceil_div(H, GEMM_BN_STORE) * 4);
     // packed-operand GEMMs: h and the gathered x hold one 256-row block per tile; every expert's weights
     // are re-laid out once per call
     p->off_h = take(packed_a_bytes(p->max_tiles * GEMM_BM, F));
@@ -342,6 +378,17 @@ int plan_skip(int64_t T, int E, int H, int F, moep_dtype dt, int ks, SkipPlan* p
   p->off_slot_out = take(with_slot_out ? (size_t)p->max_slots * H * 4 : 0);
   p->total = off > 0 ? off : 256;
   return MOEP_OK;
+}
+
+// Tile order tables of the two grouped projections (bf16 path), from the tile map scan_kernel has just written.
+static void launch_order_tables(const SkipPlan& p, char* ws, hipStream_t s) {
+  if (!p.packed) return;
+  const int32_t* expert_first = (const int32_t*)(ws + p.off_seg_end) + p.E;
+  const int n_up = (int)ceil_div(p.F, GEMM_BN_SWIGLU), n_down = (int)ceil_div(p.H, GEMM_BN_STORE);
+  hipLaunchKernelGGL(order_kernel, dim3((unsigned)ceil_div(p.max_tiles * n_up, 256)), dim3(256), 0, s, expert_first, p.E,
+                     n_up, GEMM_GROUP_M_SWIGLU, (uint32_t*)(ws + p.off_order_up));
+  hipLaunchKernelGGL(order_kernel, dim3((unsigned)ceil_div(p.max_tiles * n_down, 256)), dim3(256), 0, s, expert_first, p.E,
+                     n_down, GEMM_GROUP_M_STORE, (uint32_t*)(ws + p.off_order_down));
 }
 
 int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_mask, float beta, uint8_t* skip_mask,
@@ -359,6 +406,7 @@ int launch_skip_routing(const SkipPlan& p, const float* logits, uint32_t kept_ma
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, counts, n_blocks, p.E,
                      (int32_t*)(ws + p.off_seg_end), (int32_t*)(ws + p.off_tile_expert),
                      (int32_t*)(ws + p.off_tile_row0), (int)p.max_tiles);
+  launch_order_tables(p, ws, s);
   hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)n_blocks), dim3(RB), 0, s, top2, tw, skip_mask,
                      counts, T, p.E, (int32_t*)(ws + p.off_slot_token),
                      (float*)(ws + p.off_slot_scale), (int32_t*)(ws + p.off_slot_dest), pos);
@@ -414,6 +462,7 @@ int launch_skip_topk_routing(const SkipPlan& p, const float* logits, uint32_t ke
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, counts, n_blocks, p.E,
                      (int32_t*)(ws + p.off_seg_end), (int32_t*)(ws + p.off_tile_expert),
                      (int32_t*)(ws + p.off_tile_row0), (int)p.max_tiles);
+  launch_order_tables(p, ws, s);
 #define MOEP_SCATTER_CASE(KK)                                                                  \
   case KK:                                                                                    \
     hipLaunchKernelGGL(scatter_topk_kernel<KK>, dim3((unsigned)n_blocks), dim3(RB), 0, s, topk, tw, \
