@@ -507,7 +507,6 @@ static int forward_pruned_skip(const void* x, const void* Wgate, const void* W1,
   if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   char* w = (char*)ws;
-  const size_t es = dtype_size(dt);
 
   float* logits = logits_out ? logits_out : (float*)(w + p.off_logits);
   if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
@@ -516,7 +515,6 @@ static int forward_pruned_skip(const void* x, const void* Wgate, const void* W1,
   // bf16: the down projection writes the output of every token routed to a single expert itself
   void* direct = dt == MOEP_BF16 ? out : nullptr;
   if (int st = run_routed_ffn(p, x, W1, W3, W2, dt, w, s, nullptr, packed, direct)) return st;
-  (void)es;
   return launch_skip_combine(p, dt, skip_mask, out, w, s, direct != nullptr);
 }
 
