@@ -35,6 +35,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # profiles/hot_path_C3_hbm_traffic.txt.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {"C3": 97.7e9, "C2": None, "C4": None}   # C3: measured on commit 456a12d
 PEAK_ALU_LANE_OPS = 256 * 64 * 2.4e9   # CUs x lanes x clock: plain (non-packed) fp32/int lane operations per second
+PEAK_LDS_LOOKUPS = 256 * 32 * 2.4e9    # CUs x LDS banks x clock: 4-byte LDS look-ups per second without bank conflicts
 
 
 def parse():
@@ -183,7 +184,14 @@ def main():
     def pair_ops(r):
         n_act = min(E, min(k, r) + E - r)
         return 4 * n_act + n_act * (n_act + 3) // 2 + 8
-    score_ops = float(sum(math.comb(E, r) * T * pair_ops(r) for r in cfg.rs))
+    # (the library scores through per-token selection tables when there are many subsets and few selections per token;
+    #  those launches are timed under another name and are bound by LDS look-ups: one per nibble of the kept mask,
+    #  one for the selection index, one for the error)
+    def uses_tables(r):
+        n_act, kk = min(E, min(k, r) + E - r), min(k, r)
+        return math.comb(E, r) >= 512 and n_act <= 12 and math.comb(n_act, kk) <= 512
+    score_ops = float(sum(math.comb(E, r) * T * pair_ops(r) for r in cfg.rs if not uses_tables(r)))
+    lookups = float(sum(math.comb(E, r) * T * ((E + 3) // 4 + 2) for r in cfg.rs if uses_tables(r)))
     work_per_step = {   # kernel -> (bound, algorithmic flops, bytes or lane operations per STEP, all launches together)
         "gemm_gate_up_swiglu": ("mfma", 4.0 * T * H * F * E),
         "gemm_down": ("mfma", 2.0 * T * H * F * E),
@@ -191,6 +199,7 @@ def main():
         "gemm_down_routed": ("mfma", 2.0 * slots * H * F),
         "gram": ("hbm", float(E) * T * H * es + 4.0 * T * E * E),
         "subset_score": ("alu", score_ops),
+        "subset_score_tables": ("lds", lookups),
         "router_logits": ("hbm", None),      # launched with two different T: reported as time only
     }
     kernels = {}
@@ -207,6 +216,9 @@ def main():
             if bound == "alu":
                 a = w / (avg_ms * 1e-3)
                 entry.update(bound="alu", achieved=a, peak=PEAK_ALU_LANE_OPS, unit="lane-op/s", frac=a / PEAK_ALU_LANE_OPS)
+            elif bound == "lds":
+                a = w / (avg_ms * 1e-3)
+                entry.update(bound="lds", achieved=a, peak=PEAK_LDS_LOOKUPS, unit="look-up/s", frac=a / PEAK_LDS_LOOKUPS)
             elif bound == "mfma":
                 a = w / (avg_ms * 1e-3) / 1e12
                 entry.update(bound="mfma", achieved=a, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s",
@@ -236,7 +248,7 @@ def main():
                                        "median of 5 launches of %.1f ms" % ceiling_ms[len(ceiling_ms) // 2]}
 
     gemm_ms = sum(timing[n][0] for n in ("gemm_gate_up_swiglu", "gemm_down")) / args.steps
-    enum_names = ("gram", "routing_prep", "subset_score", "loss_reduce_argmin")
+    enum_names = ("gram", "routing_prep", "subset_score", "subset_score_tables", "loss_reduce_argmin")
     enum_ms = sum(timing[n][0] for n in enum_names if n in timing) / args.steps
     skip_names = ("gemm_gate_up_swiglu_routed", "gemm_down_routed", "skip_route_dispatch", "skip_combine")
     skip_ms = sum(timing[n][0] for n in skip_names if n in timing) / args.steps

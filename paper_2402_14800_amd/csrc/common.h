@@ -129,8 +129,10 @@ struct EnumPlan {
   int rec_floats;    // floats per token record
   int tok_tile;      // tokens per scoring block
   int64_t n_tok_tiles;
+  bool use_lut;      // many subsets, few selections per token: score through per-token selection tables
+  int n_combo;       // C(n_act, kk): selections per token
   // workspace carving (byte offsets)
-  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, total;
+  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, off_qtab, off_sel, total;
 };
 int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p);
 // Expert outputs of the rank-limited pass: row slot_of[t, j] of Y is the output of expert

@@ -18,6 +18,12 @@
 //               (scalar loads); each lane walks the rank positions, takes the first min(k,r) whose
 //               expert is in its mask, forms d explicitly and evaluates d^T G d.  A pair whose
 //               selection equals the full top-k contributes exactly 0 and is counted.
+//   score (many subsets)  A token's error depends on the subset only through WHICH of its first n_act ranked experts
+//               are kept, and then only through the first min(k,r) of those: C(n_act, min(k,r)) possible selections per
+//               token against C(E,r) subsets (495 against 12870 for E = 16, k = 4, r = 8).  qtable evaluates the error
+//               of every selection once per token; score_lut then needs, per (subset, token), a few table look-ups:
+//               kept mask -> pattern of kept rank positions (nibble tables built per token from its order),
+//               pattern -> selection index (one table per launch), selection index -> error.
 //   reduce      loss[i] = sum over token tiles of the partial sums, in a fixed order (fp64 adds).
 //   argmin      lowest index attaining the minimum; its mask by lexicographic unranking.
 #include "common.h"
@@ -377,6 +383,147 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
   }
 }
 
+// ------------------------------------------------------------------ scoring through per-token selection tables
+// Rank of the selection made by the kept-position pattern `pat` (bit j = the token's j-th ranked expert is kept):
+// the first kk set bits, as a kk-subset of the n_act positions, indexed in lexicographic order (index 0 = positions
+// 0 .. kk-1 = the selection of the full layer when kk = k).  Patterns with fewer than kk bits never occur.
+__global__ __launch_bounds__(256) void selidx_kernel(int n_act, int kk, uint16_t* __restrict__ sel) {
+  const uint32_t pat = blockIdx.x * 256 + threadIdx.x;
+  if (pat >= (1u << n_act)) return;
+  uint32_t idx = 0;
+  int rem = kk;
+  for (int j = 0; j < n_act && rem > 0; ++j) {
+    if ((pat >> j) & 1u) --rem;
+    else idx += c_binom.v[n_act - 1 - j][rem - 1];     // all selections whose next position is j come first
+  }
+  sel[pat] = rem == 0 ? (uint16_t)idx : (uint16_t)0;
+}
+
+// One workgroup per token: the error d^T G d of every selection (kk of the first n_act rank positions), the same
+// arithmetic as score_kernel's.  Selection 0 is the full layer's when kk = kfull: exactly 0.
+template <int CAP, bool EXACT>
+__global__ __launch_bounds__(256) void qtable_kernel(const float* __restrict__ rec, int kk, int kfull, int n_act_rt,
+                                                     int n_combo, float* __restrict__ qtab) {
+  constexpr int RS = rec_size(CAP);
+  const int n_act = EXACT ? CAP : n_act_rt;
+  constexpr int OFF_L = CAP, OFF_A = 2 * CAP, OFF_G = 3 * CAP;
+  const int64_t t = blockIdx.x;
+  const float* R = rec + t * RS;                        // wave-uniform
+  float ex[CAP], aw[CAP];
+#pragma unroll
+  for (int j = 0; j < CAP; ++j) { ex[j] = R[j]; aw[j] = R[OFF_A + j]; }
+  for (int c = threadIdx.x; c < n_combo; c += blockDim.x) {
+    const uint32_t bits = unrank_device(n_act, kk, (uint32_t)c);
+    float w[CAP];
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < CAP; ++j) {
+      w[j] = (j < n_act && ((bits >> j) & 1u)) ? ex[j] : 0.f;
+      sum += w[j];
+    }
+    if (sum < 1e-30f) {                                  // see score_kernel
+      float m = 0.f;
+      bool have = false;
+#pragma unroll
+      for (int j = 0; j < CAP; ++j)
+        if (j < n_act && ((bits >> j) & 1u) && !have) { m = R[OFF_L + j]; have = true; }
+      sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < CAP; ++j) {
+        w[j] = (j < n_act && ((bits >> j) & 1u)) ? __expf(R[OFF_L + j] - m) : 0.f;
+        sum += w[j];
+      }
+    }
+    const float inv = __builtin_amdgcn_rcpf(sum);
+    float d[CAP];
+#pragma unroll
+    for (int j = 0; j < CAP; ++j) d[j] = fmaf(w[j], inv, -aw[j]);
+    float q = 0.f;
+    int gi = OFF_G;
+#pragma unroll
+    for (int i = 0; i < CAP; ++i) {
+      float u = 0.f;
+#pragma unroll
+      for (int j = i; j < CAP; ++j, ++gi) u = fmaf(R[gi], d[j], u);
+      q = fmaf(d[i], u, q);
+    }
+    qtab[t * n_combo + c] = (c == 0 && kk == kfull) ? 0.f : q;
+  }
+}
+
+// Lane = LUT_SPL subsets, loop over a tile of tokens, LUT_TG tokens per barrier (double-buffered in LDS).
+constexpr int LUT_SPL = 8, LUT_TG = 8, LUT_MAX_ACT = 12, LUT_MAX_COMBO = 512;
+template <int NIB>    // nibbles of the kept mask: ceil(E / 4)
+__global__ __launch_bounds__(256) void score_lut_kernel(const float* __restrict__ rec, const float* __restrict__ qtab,
+                                                        const uint16_t* __restrict__ sel, int64_t T, int tok_tile,
+                                                        int E, int r, int n_act, int n_combo, int rec_floats,
+                                                        int ord_off, bool count_same, uint32_t n_sub,
+                                                        float* __restrict__ partial,
+                                                        uint32_t* __restrict__ partial_cnt) {
+  __shared__ uint16_t s_sel[1 << LUT_MAX_ACT];
+  __shared__ uint16_t s_nib[2][LUT_TG][NIB * 16];
+  __shared__ float s_q[2][LUT_TG * LUT_MAX_COMBO];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < (1 << n_act); i += 256) s_sel[i] = sel[i];
+  uint32_t mask[LUT_SPL];
+  float total[LUT_SPL];
+  uint32_t same_cnt[LUT_SPL];
+#pragma unroll
+  for (int s = 0; s < LUT_SPL; ++s) {
+    const uint32_t sub = (blockIdx.x * LUT_SPL + s) * 256 + tid;
+    mask[s] = sub < n_sub ? unrank_device(E, r, sub) : 0xffffffffu;    // idle lanes keep every expert
+    total[s] = 0.f;
+    same_cnt[s] = 0;
+  }
+  const int64_t t_begin = (int64_t)blockIdx.y * tok_tile;
+  const int64_t t_end = t_begin + tok_tile < T ? t_begin + tok_tile : T;
+  int buf = 0;
+  for (int64_t g0 = t_begin; g0 < t_end; g0 += LUT_TG, buf ^= 1) {
+    const int ntok = (int)(t_end - g0 < LUT_TG ? t_end - g0 : LUT_TG);
+    // nibble tables: entry v of nibble nb of token tk = the rank positions (below n_act) of the experts 4 nb + b
+    // with bit b of v set
+    for (int q = tid; q < ntok * NIB * 16; q += 256) {
+      const int tk = q / (NIB * 16), rem = q - tk * (NIB * 16);
+      const int nb = rem >> 4, v = rem & 15;
+      const uint32_t* ordw = (const uint32_t*)(rec + (g0 + tk) * rec_floats + ord_off);
+      uint32_t pat = 0;
+      for (int j = 0; j < n_act; ++j) {
+        const uint32_t e = (ordw[j >> 2] >> (8 * (j & 3))) & 0xffu;
+        if ((int)(e >> 2) == nb && ((v >> (e & 3)) & 1)) pat |= 1u << j;
+      }
+      s_nib[buf][tk][rem] = (uint16_t)pat;
+    }
+    // the group's selection errors: ntok x n_combo consecutive floats
+    {
+      const float* src = qtab + g0 * n_combo;
+      for (int i = tid; i < ntok * n_combo; i += 256) s_q[buf][i] = src[i];
+    }
+    __syncthreads();      // (also covers s_sel on the first pass; the other buffer is still being read by nobody:
+                          //  every thread finished its look-ups in it before it arrived at the previous barrier)
+    for (int tk = 0; tk < ntok; ++tk) {
+      const uint16_t* nib = s_nib[buf][tk];
+      const float* qrow = s_q[buf] + tk * n_combo;
+#pragma unroll
+      for (int s = 0; s < LUT_SPL; ++s) {
+        uint32_t pat = 0;
+#pragma unroll
+        for (int nb = 0; nb < NIB; ++nb) pat |= nib[nb * 16 + ((mask[s] >> (4 * nb)) & 15u)];
+        const uint32_t si = s_sel[pat];
+        total[s] += qrow[si];
+        same_cnt[s] += si == 0 ? 1u : 0u;
+      }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < LUT_SPL; ++s) {
+    const uint32_t sub = (blockIdx.x * LUT_SPL + s) * 256 + tid;
+    if (sub < n_sub) {
+      partial[(int64_t)blockIdx.y * n_sub + sub] = total[s];
+      partial_cnt[(int64_t)blockIdx.y * n_sub + sub] = count_same ? same_cnt[s] : 0u;
+    }
+  }
+}
+
 // ------------------------------------------------------------------ reduce + argmin
 __global__ __launch_bounds__(256) void zero_i64_kernel(unsigned long long* p) { *p = 0ull; }
 
@@ -472,10 +619,16 @@ int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
     return fail(MOEP_EUNSUPPORTED, "prune_enumerate: C(%d,%d) = %lld subsets exceeds 2^24", E, r, (long long)p->n_sub);
   const int cap = capacity_for(p->n_act);
   p->rec_floats = rec_size(cap);
+  // With many subsets and few possible selections per token, score through per-token selection tables.
+  const int64_t n_combo = binomial(p->n_act, p->kk);
+  p->n_combo = (int)(n_combo < (1 << 20) ? n_combo : (1 << 20));
+  p->use_lut = p->n_sub >= 512 && p->n_act <= LUT_MAX_ACT && n_combo <= LUT_MAX_COMBO;
   // Aim for a few thousand scoring workgroups; tiles of 32..256 tokens.
-  const int64_t sub_blocks = ceil_div(p->n_sub, score_threads(p->n_sub));
+  const int64_t sub_blocks = p->use_lut ? ceil_div(p->n_sub, 256 * LUT_SPL) : ceil_div(p->n_sub, score_threads(p->n_sub));
   int tile = 256;
-  while (tile > 32 && sub_blocks * ceil_div(T, tile) < 4096) tile >>= 1;
+  // (the table scorer's workgroups carry 2048 subsets each and re-read the pattern table per workgroup: fewer, longer ones)
+  const int64_t want_blocks = p->use_lut ? 1024 : 4096;
+  while (tile > 32 && sub_blocks * ceil_div(T, tile) < want_blocks) tile >>= 1;
   p->tok_tile = tile;
   p->n_tok_tiles = ceil_div(T, tile);
   if (p->n_tok_tiles > 65535) { p->tok_tile = (int)ceil_div(T, 65535); p->n_tok_tiles = ceil_div(T, p->tok_tile); }
@@ -485,6 +638,11 @@ int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
   p->off_masks = off;
   p->off_partial = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(float));
   p->off_partial_cnt = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(uint32_t));
+  p->off_qtab = p->off_sel = off;
+  if (p->use_lut) {
+    p->off_qtab = off; off += align256((size_t)T * p->n_combo * sizeof(float));
+    p->off_sel = off; off += align256(((size_t)1 << p->n_act) * sizeof(uint16_t));
+  }
   p->total = off > 0 ? off : 256;
   return MOEP_OK;
 }
@@ -555,7 +713,39 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
         hipLaunchKernelGGL(prep_kernel<32>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
       MOEP_HIP(hipGetLastError());
     }
-    {
+    if (p.use_lut) {
+      Timed t("subset_score_tables", s);
+      float* qtab = (float*)(ws + p.off_qtab);
+      uint16_t* sel = (uint16_t*)(ws + p.off_sel);
+      hipLaunchKernelGGL(selidx_kernel, dim3((unsigned)ceil_div((int64_t)1 << p.n_act, 256)), dim3(256), 0, s, p.n_act, p.kk, sel);
+      const dim3 qgrid((unsigned)p.T), qblock(p.n_combo <= 64 ? 64 : 256);
+#define MOEP_QTABLE_CASE(C)                                                                                       \
+  case C:                                                                                                         \
+    if (p.n_act == C)                                                                                             \
+      hipLaunchKernelGGL((qtable_kernel<C, true>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo, qtab); \
+    else                                                                                                          \
+      hipLaunchKernelGGL((qtable_kernel<C, false>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo, qtab); \
+    break;
+      switch (cap) {
+        MOEP_QTABLE_CASE(2) MOEP_QTABLE_CASE(4) MOEP_QTABLE_CASE(6) MOEP_QTABLE_CASE(8) MOEP_QTABLE_CASE(12)
+        default: return fail(MOEP_EUNSUPPORTED, "prune_enumerate: no selection table for %d active ranks", p.n_act);
+      }
+#undef MOEP_QTABLE_CASE
+      const dim3 grid((unsigned)ceil_div(p.n_sub, 256 * LUT_SPL), (unsigned)p.n_tok_tiles);
+      const int ord_off = rec_order_off(cap);
+      const bool count_same = p.kk == p.k;
+#define MOEP_LUT_CASE(N)                                                                                          \
+  case N:                                                                                                         \
+    hipLaunchKernelGGL(score_lut_kernel<N>, grid, dim3(256), 0, s, rec, qtab, sel, p.T, p.tok_tile, p.E, p.r,     \
+                       p.n_act, p.n_combo, p.rec_floats, ord_off, count_same, (uint32_t)p.n_sub, partial, pcnt);   \
+    break;
+      switch ((p.E + 3) / 4) {
+        MOEP_LUT_CASE(1) MOEP_LUT_CASE(2) MOEP_LUT_CASE(3) MOEP_LUT_CASE(4)
+        MOEP_LUT_CASE(5) MOEP_LUT_CASE(6) MOEP_LUT_CASE(7) MOEP_LUT_CASE(8)
+      }
+#undef MOEP_LUT_CASE
+      MOEP_HIP(hipGetLastError());
+    } else {
       Timed t("subset_score", s);
       switch (cap) {
         case 2: launch_score<2>(p, rec, partial, pcnt, s); break;

@@ -82,6 +82,12 @@ ENUM_CASES = [
     (32, 2, 31, 50, 128, "bf16"),     # the largest E
     (8, 2, 6, 200, 576, "bf16"),      # H = 512 + 64: a second, partly filled block of hidden units in the Gram pass
     (16, 4, 12, 77, 1088, "bf16"),    # the same with 16 rows per token
+    # many subsets, few possible selections per token: scored through per-token selection tables
+    (32, 2, 29, 40, 64, "bf16"),      # 4960 subsets, 5 active ranks, 8 nibbles of kept mask
+    (20, 2, 17, 60, 64, "bf16"),      # 1140 subsets, 5 nibbles
+    (12, 1, 6, 70, 64, "bf16"),       # top-1: 924 subsets, 7 selections per token
+    (12, 3, 6, 300, 64, "f32"),       # 924 subsets, 84 selections, several token groups and a ragged last one
+    (16, 4, 8, 517, 64, "bf16"),      # 12870 subsets over several token tiles
 ]
 
 
@@ -142,6 +148,24 @@ def test_prune_enumerate_ties_and_planted_argmin():
     ref2, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), 2, 2)
     assert np.all(np.isfinite(loss2))
     check_losses(loss2, ref2)
+
+
+def test_prune_enumerate_tables_with_ties_and_logits_far_below_the_maximum():
+    """The table scorer (924 subsets, 28 selections per token) on logits with exact ties and with six experts at
+    -1e9: the subset that keeps exactly those six has every survivor far below the token's maximum and needs Eq. 1
+    redone relative to the largest selected logit; the subset that keeps the other six loses nothing."""
+    E, T, H = 12, 150, 64
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, "bf16", seed=19, device=DEV)
+    low = [1, 4, 7, 9, 10, 11]
+    logits_t[:, low] = -1e9
+    logits_t[::5, 2] = logits_t[::5, 0]        # exact ties between experts 0 and 2
+    loss, amin, amask, _ = run_enumerate(logits_t, Y_t, 2, 6)
+    ref, ref_amin, masks = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), 2, 6)
+    assert len(loss) == 924 and np.all(np.isfinite(loss))
+    check_losses(loss, ref)
+    keep_high = oracle.kept_subsets(E, 6).index((0, 2, 3, 5, 6, 8))
+    assert amin == ref_amin == keep_high and loss[amin] == 0.0
+    assert loss[oracle.kept_subsets(E, 6).index(tuple(low))] > 0.0
 
 
 def test_prune_enumerate_relabelling_and_scale():
