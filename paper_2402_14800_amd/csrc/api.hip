@@ -258,7 +258,6 @@ static int expert_outputs(const void* x, const void* Wgate, const void* W1, cons
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t es = dtype_size(dt);
 
-  if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   if (dt == MOEP_BF16) {
     // Operands are packed once per call into the blocked layout of the packed GEMM (x; every expert's
     // weights, unless the caller has done that already); h stays in that layout between the two projections
@@ -269,7 +268,13 @@ static int expert_outputs(const void* x, const void* Wgate, const void* W1, cons
     char* xp = hp + align256((size_t)eb * h_bytes);
     const char* wgu = xp + align256(packed_a_bytes(T, H));
     const char* wdn = wgu + align256((size_t)E * packed_b_bytes(F, H, true));
-    if (int st = launch_pack_a_bf16(x, H, T, H, xp, s, "pack_x")) return st;
+    // one pass over x for the router logits and its packed copy where a fused kernel exists
+    int st_x = launch_router_and_pack_x(x, Wgate, T, E, H, logits, xp, s);
+    if (st_x == MOEP_EUNSUPPORTED) {
+      if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
+      st_x = launch_pack_a_bf16(x, H, T, H, xp, s, "pack_x");
+    }
+    if (st_x) return st_x;
     if (packed) {                     // all W1/W3 pairs, then all W2
       wgu = (const char*)packed;
       wdn = wgu + (size_t)E * packed_b_bytes(F, H, true);
@@ -293,6 +298,7 @@ static int expert_outputs(const void* x, const void* Wgate, const void* W1, cons
     }
     return MOEP_OK;
   }
+  if (int st = launch_router(x, Wgate, T, E, H, dt, logits, s)) return st;
   for (int e = 0; e < E; ++e) {
     GemmArgs up;                                  // h = silu(x W1[e]^T) * (x W3[e]^T)
     up.A = x; up.lda = H;

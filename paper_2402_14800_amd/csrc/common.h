@@ -119,6 +119,10 @@ int launch_gemm_bf16_packed(const PackedGemmArgs& g, hipStream_t s, const char* 
 // ---- router -------------------------------------------------------------------
 int launch_router(const void* x, const void* Wgate, int64_t T, int E, int H, moep_dtype dt,
                   float* logits, hipStream_t s);
+// bf16: the same logits (bit for bit) and the packed A-operand copy of x in one pass; MOEP_EUNSUPPORTED, with nothing
+// launched and no message, for shapes without a fused kernel
+int launch_router_and_pack_x(const void* x, const void* Wgate, int64_t T, int E, int H, float* logits, void* xpacked,
+                             hipStream_t s);
 
 // ---- enumeration ----------------------------------------------------------------
 struct EnumPlan {

@@ -100,17 +100,26 @@ __global__ __launch_bounds__(256) void router_kernel(const void* __restrict__ x,
 typedef __attribute__((ext_vector_type(8))) __bf16 r_bf16x8;
 typedef __attribute__((ext_vector_type(4))) float r_f32x4;
 
+// PACK: the wavefront also writes its 16 rows of x in the blocked operand layout of the packed GEMM (see
+// gemm_bf16_packed.hip: tile of 256 rows, slice of 32 hidden units, row p of a block = 64 bytes whose 16-byte chunk c
+// sits at position c ^ ((p >> 2) & 3)) -- the registers it feeds the MFMA with are exactly one row group of a block,
+// 1 KB of consecutive bytes per store -- so that the expert pass reads x once for both.  Row groups beyond T, up to
+// the end of the last tile, are filled with the last row (their products are never stored).
+template <bool PACK>
 __global__ __launch_bounds__(256) void router_mfma_kernel(const uint4* __restrict__ x,
                                                           const uint4* __restrict__ Wgate,
                                                           float* __restrict__ logits, int64_t T, int E,
-                                                          int H) {
+                                                          int H, uint4* __restrict__ xpacked) {
   const int lane = threadIdx.x & 63;
   const int64_t t0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 16;
-  if (t0 >= T) return;
+  if (t0 >= (PACK ? (T + 255) / 256 * 256 : T)) return;
   const int row = lane & 15, kg = lane >> 4;
   const int chunks = H / 8;
   const int64_t t = t0 + row < T ? t0 + row : T - 1;
   const uint4* xp = x + t * chunks + kg;
+  // packed destination of this lane's chunk of slice 0; consecutive slices are 1024 chunks (16 KB) apart
+  const int p_row = (int)((t0 + row) & 255);
+  uint4* const dst = PACK ? xpacked + ((t0 >> 8) * (int64_t)(H / 32)) * 1024 + p_row * 4 + (kg ^ ((p_row >> 2) & 3)) : nullptr;
   const bool w_valid = row < E;
   const uint4* wp = Wgate + (int64_t)(w_valid ? row : 0) * chunks + kg;
   r_f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
@@ -122,6 +131,7 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint4* __restric
       const bool in = s0 + i < steps;
       xv[i] = in ? xp[(s0 + i) * 4] : make_uint4(0, 0, 0, 0);
       wv[i] = (in && w_valid) ? wp[(s0 + i) * 4] : make_uint4(0, 0, 0, 0);
+      if (PACK && in) dst[(int64_t)(s0 + i) * 1024] = xv[i];
     }
 #pragma unroll
     for (int i = 0; i < 8; i += 2) {
@@ -140,13 +150,15 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint4* __restric
   }
 }
 
+bool mfma_router_applies(int E, int H) { return E <= 16 && H % 32 == 0; }
+
 template <bool BF16>
 int launch_t(const void* x, const void* Wgate, int64_t T, int E, int H, float* logits, hipStream_t s) {
-  if (BF16 && E <= 16 && H % 32 == 0) {
+  if (BF16 && mfma_router_applies(E, H)) {
     const int64_t blocks = ceil_div(T, 64);
     if (blocks < ((int64_t)1 << 31)) {
-      hipLaunchKernelGGL(router_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)x,
-                         (const uint4*)Wgate, logits, T, E, H);
+      hipLaunchKernelGGL(router_mfma_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)x,
+                         (const uint4*)Wgate, logits, T, E, H, (uint4*)nullptr);
       MOEP_HIP(hipGetLastError());
       return MOEP_OK;
     }
@@ -170,6 +182,22 @@ int launch_router(const void* x, const void* Wgate, int64_t T, int E, int H, moe
   Timed t("router_logits", s);
   return dt == MOEP_BF16 ? launch_t<true>(x, Wgate, T, E, H, logits, s)
                          : launch_t<false>(x, Wgate, T, E, H, logits, s);
+}
+
+// bf16: router logits and the packed copy of x in one pass over x.  Returns MOEP_EUNSUPPORTED without launching
+// anything when the shape has no fused kernel (the caller then runs the router and the packing separately).
+int launch_router_and_pack_x(const void* x, const void* Wgate, int64_t T, int E, int H, float* logits, void* xpacked,
+                             hipStream_t s) {
+  if (T <= 0) return MOEP_OK;
+  const int64_t blocks = ceil_div(ceil_div(T, 256) * 256, 64);
+  if (!mfma_router_applies(E, H) || H % 64 || blocks >= ((int64_t)1 << 31)) return MOEP_EUNSUPPORTED;
+  if (((uintptr_t)x | (uintptr_t)Wgate | (uintptr_t)xpacked) & 15)
+    return fail(MOEP_EUNSUPPORTED, "router: x, Wgate and the packed copy of x must be 16-byte aligned");
+  Timed t("router_logits_pack_x", s);
+  hipLaunchKernelGGL(router_mfma_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)x,
+                     (const uint4*)Wgate, logits, T, E, H, (uint4*)xpacked);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
 }
 
 }  // namespace moep
