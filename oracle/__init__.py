@@ -19,6 +19,7 @@ from .moe_reference import (  # noqa: F401
     pruned_layer_output,
     prune_enumerate,
     prune_enumerate_streamed,
+    prune_enumerate_gram_form,
     skip_decision,
     forward_skip,
     median_skip_ratio,

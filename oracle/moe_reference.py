@@ -156,6 +156,41 @@ def prune_enumerate(logits: np.ndarray, Y: np.ndarray, k: int, r: int):
     return loss, int(np.argmin(loss)), masks
 
 
+def prune_enumerate_gram_form(logits: np.ndarray, Y: np.ndarray, k: int, r: int):
+    """Eq. 3 for every kept set of size r, evaluated in fp64 through the per-token Gram matrix.
+
+    A SECOND oracle, for sizes the direct definition above cannot reach in seconds (thousands of
+    subsets over thousands of tokens): with a = Eq. 1 weights of the full layer, b = those of the
+    layer pruned to C and d = b - a, F'(x_t, C) - F(x_t) = sum_e d_e E_e(x_t), hence its squared
+    norm is d^T G_t d with G_t = Y_t Y_t^T.  The same real number as `prune_enumerate`, never the
+    primary reference: a test pins it to `prune_enumerate` on small inputs, and results checked
+    against it are labelled as such.  d is formed explicitly (expanding the quadratic form in a
+    and b separately would cancel), and a token whose selection is unchanged contributes 0 exactly.
+
+    Returns loss [C(E,r)], argmin, masks like `prune_enumerate`.
+    """
+    logits = np.asarray(logits, dtype=np.float64)
+    Y = np.asarray(Y, dtype=np.float64)
+    E, T, _ = Y.shape
+    if not (1 <= r <= E and 1 <= k <= E):
+        raise ValueError("need 1 <= r <= E and 1 <= k <= E")
+    G = np.einsum("eth,fth->tef", Y, Y)                          # [T,E,E]
+    order = routing_order(logits)
+    sel_full = _first_in_order(order, np.ones(E, dtype=bool), min(k, E))
+    a = renormalised_weights(logits, sel_full)
+    subsets = kept_subsets(E, r)
+    loss = np.empty(len(subsets), dtype=np.float64)
+    for i, kept in enumerate(subsets):
+        allowed = np.zeros(E, dtype=bool)
+        allowed[list(kept)] = True
+        sel = _first_in_order(order, allowed, min(k, r))
+        d = renormalised_weights(logits, sel) - a
+        d[np.all(sel == sel_full, axis=1)] = 0.0                  # unchanged routing: exactly nothing
+        loss[i] = np.einsum("te,tef,tf->", d, G, d)
+    masks = np.array([subset_mask(c) for c in subsets], dtype=np.uint32)
+    return loss, int(np.argmin(loss)), masks
+
+
 def prune_enumerate_streamed(logits, Y, k: int, r: int, chunk: int = 8192, to_f64=None):
     """`prune_enumerate` over token chunks, summed: Eq. 3 is a sum over tokens.
 

@@ -415,11 +415,14 @@ def test_config3_expert_outputs_one_row_per_tile(config3):
         sampled_expert_check(layer, logits_t, Y_t, torch.tensor(part, device=DEV), W64)
 
 
-def enumeration_windows_check(logits_t, Y_t, k, r, windows, loss, unaff):
+def enumeration_windows_check(logits_t, Y_t, k, r, windows, loss, unaff, gram_form_windows=()):
     """Cuts the tokens at the ends of `windows` (token ranges), enumerates every piece on its own and checks
     (a) the pieces inside `windows` against the oracle (Sec. 3.2, Eq. 3), and (b) that all pieces add up to
-    the full call's losses and unaffected-pair count, which ties the oracle-checked windows to the full call."""
+    the full call's losses and unaffected-pair count, which ties the oracle-checked windows to the full call.
+    Pieces in `gram_form_windows` (longer ones) are checked against the SECOND oracle, the fp64 Gram form that a
+    CPU test pins to the direct definition."""
     T = logits_t.shape[0]
+    windows = list(windows) + list(gram_form_windows)
     cuts = sorted({0, T} | {a for a, _ in windows} | {b for _, b in windows})
     total = np.zeros_like(loss)
     total_unaff = 0
@@ -428,7 +431,8 @@ def enumeration_windows_check(logits_t, Y_t, k, r, windows, loss, unaff):
         total += lp
         total_unaff += up
         if (a, b) in windows:
-            ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[a:b]), wl.to_f64(Y_t[:, a:b]), k, r)
+            enumerate_ref = oracle.prune_enumerate_gram_form if (a, b) in gram_form_windows else oracle.prune_enumerate
+            ref, _, _ = enumerate_ref(wl.to_f64(logits_t[a:b]), wl.to_f64(Y_t[:, a:b]), k, r)
             check_losses(lp, ref)
             check_argmin(ap, ref, lp)
     np.testing.assert_allclose(total, loss, rtol=2e-5)
@@ -510,7 +514,8 @@ def test_config4_enumeration_stress(config4):
     load = torch.bincount(torch.topk(logits_b, k, dim=1).indices.flatten(), minlength=E).float()
     assert load.max() > 1.5 * load.min()                     # experts are unequally used
     assert tie_free(logits_b.cpu().numpy())
-    # windows sized so that the oracle needs well under a minute per r: head, unaligned middle, tail
+    # windows sized so that the oracle needs well under a minute per r: head, unaligned middle, tail; and a longer
+    # unaligned one in the second half against the Gram-form oracle
     for r, (w_head, w_mid, w_tail) in ((12, (768, 517, 700)), (8, (192, 131, 150))):
         loss, amin, amask, unaff = run_enumerate(logits_b, Y_t, k, r)
         assert len(loss) == math.comb(E, r)
@@ -518,7 +523,8 @@ def test_config4_enumeration_stress(config4):
         assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(E, r, amin)
         mid = T // 3 + 7
         windows = [(0, w_head), (mid, mid + w_mid), (T - w_tail, T)]
-        enumeration_windows_check(logits_b, Y_t, k, r, windows, loss, unaff)
+        enumeration_windows_check(logits_b, Y_t, k, r, windows, loss, unaff,
+                                  gram_form_windows=[(2 * T // 3 + 5, 2 * T // 3 + 5 + 8197)])
 
 
 # ------------------------------------------------------------------ pruned + skipping forward

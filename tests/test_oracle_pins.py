@@ -240,6 +240,22 @@ def test_quadratic_form_identity():
         assert loss[i] == pytest.approx(total, rel=1e-10)
 
 
+@pytest.mark.parametrize("E,k,r,T,H", [(6, 2, 3, 40, 9), (8, 3, 5, 30, 5), (5, 1, 2, 25, 4), (7, 4, 2, 20, 6), (6, 2, 6, 10, 3)])
+def test_gram_form_oracle_is_pinned_to_the_direct_definition(E, k, r, T, H):
+    # the second oracle (per-token Gram matrix, fp64) against the direct definition, with ties and a
+    # never-selected expert thrown in; identical argmin and masks, losses to 1e-10
+    logits, Y = enumeration_case(23 + E + r, T=T, E=E, H=H)
+    logits[::4, 1] = logits[::4, 0]
+    logits[:, E - 1] = -1e9
+    direct, amin, masks = oracle.prune_enumerate(logits, Y, k, r)
+    gram, amin_g, masks_g = oracle.prune_enumerate_gram_form(logits, Y, k, r)
+    np.testing.assert_allclose(gram, direct, rtol=1e-10, atol=1e-12 * max(direct.max(), 1.0))
+    assert np.array_equal(masks, masks_g)
+    assert amin_g == amin or direct[amin_g] == pytest.approx(direct[amin], rel=1e-10)
+    if r == E:
+        assert gram.tolist() == [0.0]
+
+
 def test_planted_argmin():
     # Experts 1 and 4 get logits of -1e9 on every token: they are never routed to, so the
     # subset that drops exactly those two reproduces the layer and is the argmin with loss 0.
