@@ -199,6 +199,8 @@ EXPERT_CASES = [
     ("bf16", 1, 64, 64, 76837),      # more tiles than compute units, K shorter than the load-ahead distance
     ("bf16", 2, 192, 448, 66000),    # several tiles per workgroup in both GEMMs, ragged last tile
     ("bf16", 1, 128, 320, 66000),    # several tiles per workgroup with K = 4 and 10 slices (the load-ahead distance and twice the ring)
+    ("bf16", 20, 64, 64, 300),       # more than 16 experts: the router's second MFMA, batched launches over 20 experts
+    ("bf16", 32, 128, 64, 77),       # the largest E
 ]
 
 
@@ -505,7 +507,11 @@ def test_config4_expert_outputs_one_row_per_tile(config4):
     sampled_expert_check(layer, logits_t, Y_t, torch.tensor(tokens, device=DEV), weights_f64(layer))
 
 
-def test_config4_enumeration_stress(config4):
+# windows sized so that the CPU oracle needs about two minutes per r at most (a GPU run that prints nothing for three
+# minutes is taken to be hung): head, unaligned middle and tail against the direct definition, and a longer unaligned
+# one in the second half against the Gram-form oracle
+@pytest.mark.parametrize("r,w_head,w_mid,w_tail,w_gram", [(12, 768, 517, 700, 8197), (8, 128, 67, 96, 2051)])
+def test_config4_enumeration_stress(config4, r, w_head, w_mid, w_tail, w_gram):
     """Both r of the stress configuration on the GPU's own expert outputs, the per-expert logit bias added by the
     harness between the two calls as the configuration says."""
     cfg, layer, logits_t, Y_t = config4
@@ -514,17 +520,14 @@ def test_config4_enumeration_stress(config4):
     load = torch.bincount(torch.topk(logits_b, k, dim=1).indices.flatten(), minlength=E).float()
     assert load.max() > 1.5 * load.min()                     # experts are unequally used
     assert tie_free(logits_b.cpu().numpy())
-    # windows sized so that the oracle needs well under a minute per r: head, unaligned middle, tail; and a longer
-    # unaligned one in the second half against the Gram-form oracle
-    for r, (w_head, w_mid, w_tail) in ((12, (768, 517, 700)), (8, (192, 131, 150))):
-        loss, amin, amask, unaff = run_enumerate(logits_b, Y_t, k, r)
-        assert len(loss) == math.comb(E, r)
-        assert unaff == T * math.comb(E - k, r - k)
-        assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(E, r, amin)
-        mid = T // 3 + 7
-        windows = [(0, w_head), (mid, mid + w_mid), (T - w_tail, T)]
-        enumeration_windows_check(logits_b, Y_t, k, r, windows, loss, unaff,
-                                  gram_form_windows=[(2 * T // 3 + 5, 2 * T // 3 + 5 + 8197)])
+    loss, amin, amask, unaff = run_enumerate(logits_b, Y_t, k, r)
+    assert len(loss) == math.comb(E, r)
+    assert unaff == T * math.comb(E - k, r - k)
+    assert amin == int(np.argmin(loss)) and amask == pkg.subset_unrank(E, r, amin)
+    mid = T // 3 + 7
+    windows = [(0, w_head), (mid, mid + w_mid), (T - w_tail, T)]
+    enumeration_windows_check(logits_b, Y_t, k, r, windows, loss, unaff,
+                              gram_form_windows=[(2 * T // 3 + 5, 2 * T // 3 + 5 + w_gram)])
 
 
 # ------------------------------------------------------------------ pruned + skipping forward
