@@ -348,6 +348,17 @@ def main():
             "kernels_ms": {n: v[0] / v[1] for n, v in sorted(rk_timing.items())},
         }
         del ws_rk, rk_out
+    if args.workload == "C3":
+        # The paper's own figures for this path, as context only: other hardware, the whole 32-layer model, and its wall
+        # times include the calibration forward (Sec. 4.1 for the pruning times, the speed-up table of Sec. 4 for skipping).
+        out["paper_context"] = {
+            "expert_pruning_wall_time": "about 30 min (r=6) and 90 min (r=4) for all 32 MoE layers of Mixtral 8x7B on "
+                                        "128 x 2048 calibration tokens; hardware not stated for that run (A100-80G "
+                                        "elsewhere in the paper)",
+            "derived_subset_tokens_per_s_per_layer": {"r=6": 28 * 262144 / (1800.0 / 32), "r=4": 70 * 262144 / (5400.0 / 32)},
+            "dynamic_skipping_generation_speedup": 1.08,
+            "note": "context, not a target: vs_baseline stays null",
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layer, Y, logits_b, torch, wl)
     print(json.dumps(out))
