@@ -185,13 +185,13 @@ def main():
         n_act = min(E, min(k, r) + E - r)
         return 4 * n_act + n_act * (n_act + 3) // 2 + 8
     # (the library scores through per-token selection tables when there are many subsets and few selections per token;
-    #  those launches are timed under another name and are bound by LDS look-ups: one per nibble of the kept mask,
-    #  one for the selection index, one for the error)
+    #  those launches are timed under another name and are bound by LDS look-ups: per pair half a look-up per nibble of
+    #  the kept mask (one 32-bit entry serves two tokens), one for the selection index, one for the error)
     def uses_tables(r):
         n_act, kk = min(E, min(k, r) + E - r), min(k, r)
         return math.comb(E, r) >= 512 and n_act <= 12 and math.comb(n_act, kk) <= 512
     score_ops = float(sum(math.comb(E, r) * T * pair_ops(r) for r in cfg.rs if not uses_tables(r)))
-    lookups = float(sum(math.comb(E, r) * T * ((E + 3) // 4 + 2) for r in cfg.rs if uses_tables(r)))
+    lookups = float(sum(math.comb(E, r) * T * ((E + 3) // 4 / 2 + 2) for r in cfg.rs if uses_tables(r)))
     work_per_step = {   # kernel -> (bound, algorithmic flops, bytes or lane operations per STEP, all launches together)
         "gemm_gate_up_swiglu": ("mfma", 4.0 * T * H * F * E),
         "gemm_down": ("mfma", 2.0 * T * H * F * E),

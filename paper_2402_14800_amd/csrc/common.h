@@ -135,8 +135,9 @@ struct EnumPlan {
   int64_t n_tok_tiles;
   bool use_lut;      // many subsets, few selections per token: score through per-token selection tables
   int n_combo;       // C(n_act, kk): selections per token
+  int lut_spl;       // subsets per lane of the table scorer (0 without it)
   // workspace carving (byte offsets)
-  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, off_qtab, off_sel, total;
+  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, off_qtab, off_sel, off_nib, total;
 };
 int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p);
 // Expert outputs of the rank-limited pass: row slot_of[t, j] of Y is the output of expert

@@ -386,7 +386,7 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
 // ------------------------------------------------------------------ scoring through per-token selection tables
 // Rank of the selection made by the kept-position pattern `pat` (bit j = the token's j-th ranked expert is kept):
 // the first kk set bits, as a kk-subset of the n_act positions, indexed in lexicographic order (index 0 = positions
-// 0 .. kk-1 = the selection of the full layer when kk = k).  Patterns with fewer than kk bits never occur.
+// 0 .. kk-1 = the selection of the full layer when kk = k).  Patterns with fewer than kk bits belong to no subset.
 __global__ __launch_bounds__(256) void selidx_kernel(int n_act, int kk, uint16_t* __restrict__ sel) {
   const uint32_t pat = blockIdx.x * 256 + threadIdx.x;
   if (pat >= (1u << n_act)) return;
@@ -396,14 +396,15 @@ __global__ __launch_bounds__(256) void selidx_kernel(int n_act, int kk, uint16_t
     if ((pat >> j) & 1u) --rem;
     else idx += c_binom.v[n_act - 1 - j][rem - 1];     // all selections whose next position is j come first
   }
-  sel[pat] = rem == 0 ? (uint16_t)idx : (uint16_t)0;
+  sel[pat] = rem == 0 ? (uint16_t)idx : (uint16_t)1;     // too few bits: only idle lanes look these up (never index 0)
 }
 
 // One workgroup per token: the error d^T G d of every selection (kk of the first n_act rank positions), the same
 // arithmetic as score_kernel's.  Selection 0 is the full layer's when kk = kfull: exactly 0.
 template <int CAP, bool EXACT>
 __global__ __launch_bounds__(256) void qtable_kernel(const float* __restrict__ rec, int kk, int kfull, int n_act_rt,
-                                                     int n_combo, float* __restrict__ qtab) {
+                                                     int n_combo, float* __restrict__ qtab, int nib,
+                                                     uint16_t* __restrict__ nibtab) {
   constexpr int RS = rec_size(CAP);
   const int n_act = EXACT ? CAP : n_act_rt;
   constexpr int OFF_L = CAP, OFF_A = 2 * CAP, OFF_G = 3 * CAP;
@@ -449,49 +450,55 @@ __global__ __launch_bounds__(256) void qtable_kernel(const float* __restrict__ r
     }
     qtab[t * n_combo + c] = (c == 0 && kk == kfull) ? 0.f : q;
   }
+  // The token's nibble tables, which turn a kept mask into a kept-position pattern four experts at a time: entry v
+  // of nibble nb = the rank positions (below n_act) of the experts 4 nb + b with bit b of v set.  Stored as the low
+  // or high half of a 32-bit word shared with the neighbouring token, so that one look-up serves two tokens.
+  const uint32_t* ordw = (const uint32_t*)(R + rec_order_off(CAP));
+  for (int q = threadIdx.x; q < nib * 16; q += blockDim.x) {
+    const int nb = q >> 4, v = q & 15;
+    uint32_t pat = 0;
+    for (int j = 0; j < n_act; ++j) {
+      const uint32_t e = (ordw[j >> 2] >> (8 * (j & 3))) & 0xffu;
+      if ((int)(e >> 2) == nb && ((v >> (e & 3)) & 1)) pat |= 1u << j;
+    }
+    nibtab[((t >> 1) * (nib * 16) + q) * 2 + (t & 1)] = (uint16_t)pat;   // tokens 2 i and 2 i + 1 share a word
+  }
 }
 
-// Lane = LUT_SPL subsets, loop over a tile of tokens, LUT_TG tokens per barrier (double-buffered in LDS).
-constexpr int LUT_SPL = 8, LUT_TG = 8, LUT_MAX_ACT = 12, LUT_MAX_COMBO = 512;
-template <int NIB>    // nibbles of the kept mask: ceil(E / 4)
-__global__ __launch_bounds__(256) void score_lut_kernel(const float* __restrict__ rec, const float* __restrict__ qtab,
+// Lane = SPL subsets, loop over a tile of tokens, LUT_TG tokens per barrier (double-buffered in LDS).  Per pair:
+// one look-up per nibble of the kept mask (lanes of a wavefront hold neighbouring subsets: few distinct entries, no
+// bank conflicts), one of the pattern's selection index, one of that selection's error.
+constexpr int LUT_TG = 8, LUT_MAX_ACT = 12, LUT_MAX_COMBO = 512, LUT_MAX_ADDR = 68;
+template <int NIB, int SPL>    // NIB = nibbles of the kept mask: ceil(E / 4)
+__global__ __launch_bounds__(256, 3) void score_lut_kernel(const float* __restrict__ qtab,
+                                                        const uint32_t* __restrict__ nibtab,
                                                         const uint16_t* __restrict__ sel, int64_t T, int tok_tile,
-                                                        int E, int r, int n_act, int n_combo, int rec_floats,
-                                                        int ord_off, bool count_same, uint32_t n_sub,
-                                                        float* __restrict__ partial,
+                                                        int E, int r, int n_act, int n_combo, bool count_same,
+                                                        uint32_t n_sub, float* __restrict__ partial,
                                                         uint32_t* __restrict__ partial_cnt) {
+  constexpr int NT = NIB * 16;                           // nibble-table entries per token
   __shared__ uint16_t s_sel[1 << LUT_MAX_ACT];
-  __shared__ uint16_t s_nib[2][LUT_TG][NIB * 16];
+  __shared__ uint32_t s_nib[2][LUT_TG / 2 * NT];
   __shared__ float s_q[2][LUT_TG * LUT_MAX_COMBO];
   const int tid = threadIdx.x;
   for (int i = tid; i < (1 << n_act); i += 256) s_sel[i] = sel[i];
-  uint32_t mask[LUT_SPL];
-  float total[LUT_SPL];
-  uint32_t same_cnt[LUT_SPL];
+  uint32_t mask[SPL];
+  float total[SPL];
+  uint32_t same_cnt = 0;                                 // over all of the lane's subsets
 #pragma unroll
-  for (int s = 0; s < LUT_SPL; ++s) {
-    const uint32_t sub = (blockIdx.x * LUT_SPL + s) * 256 + tid;
-    mask[s] = sub < n_sub ? unrank_device(E, r, sub) : 0xffffffffu;    // idle lanes keep every expert
+  for (int s = 0; s < SPL; ++s) {
+    const uint32_t sub = (blockIdx.x * SPL + s) * 256 + tid;
+    mask[s] = sub < n_sub ? unrank_device(E, r, sub) : 0u;   // idle: empty pattern, selection index 1, not counted
     total[s] = 0.f;
-    same_cnt[s] = 0;
   }
   const int64_t t_begin = (int64_t)blockIdx.y * tok_tile;
   const int64_t t_end = t_begin + tok_tile < T ? t_begin + tok_tile : T;
   int buf = 0;
   for (int64_t g0 = t_begin; g0 < t_end; g0 += LUT_TG, buf ^= 1) {
     const int ntok = (int)(t_end - g0 < LUT_TG ? t_end - g0 : LUT_TG);
-    // nibble tables: entry v of nibble nb of token tk = the rank positions (below n_act) of the experts 4 nb + b
-    // with bit b of v set
-    for (int q = tid; q < ntok * NIB * 16; q += 256) {
-      const int tk = q / (NIB * 16), rem = q - tk * (NIB * 16);
-      const int nb = rem >> 4, v = rem & 15;
-      const uint32_t* ordw = (const uint32_t*)(rec + (g0 + tk) * rec_floats + ord_off);
-      uint32_t pat = 0;
-      for (int j = 0; j < n_act; ++j) {
-        const uint32_t e = (ordw[j >> 2] >> (8 * (j & 3))) & 0xffu;
-        if ((int)(e >> 2) == nb && ((v >> (e & 3)) & 1)) pat |= 1u << j;
-      }
-      s_nib[buf][tk][rem] = (uint16_t)pat;
+    {
+      const uint32_t* src = nibtab + (g0 >> 1) * NT;       // g0 is even
+      for (int i = tid; i < ((ntok + 1) >> 1) * NT; i += 256) s_nib[buf][i] = src[i];
     }
     // the group's selection errors: ntok x n_combo consecutive floats
     {
@@ -500,26 +507,34 @@ __global__ __launch_bounds__(256) void score_lut_kernel(const float* __restrict_
     }
     __syncthreads();      // (also covers s_sel on the first pass; the other buffer is still being read by nobody:
                           //  every thread finished its look-ups in it before it arrived at the previous barrier)
-    for (int tk = 0; tk < ntok; ++tk) {
-      const uint16_t* nib = s_nib[buf][tk];
+    for (int tk = 0; tk < ntok; tk += 2) {
+      const uint32_t* nib = s_nib[buf] + (tk >> 1) * NT;
       const float* qrow = s_q[buf] + tk * n_combo;
+      const bool pair = tk + 1 < ntok;                   // the group's last token may stand alone
 #pragma unroll
-      for (int s = 0; s < LUT_SPL; ++s) {
-        uint32_t pat = 0;
+      for (int s = 0; s < SPL; ++s) {
+        uint32_t pat = 0;                                // low half: token tk, high half: token tk + 1
 #pragma unroll
         for (int nb = 0; nb < NIB; ++nb) pat |= nib[nb * 16 + ((mask[s] >> (4 * nb)) & 15u)];
-        const uint32_t si = s_sel[pat];
-        total[s] += qrow[si];
-        same_cnt[s] += si == 0 ? 1u : 0u;
+        const uint32_t si0 = s_sel[pat & 0xffffu];
+        total[s] += qrow[si0];
+        same_cnt += si0 == 0 ? 1u : 0u;
+        if (pair) {
+          const uint32_t si1 = s_sel[pat >> 16];
+          total[s] += qrow[n_combo + si1];
+          same_cnt += si1 == 0 ? 1u : 0u;
+        }
+        // about 32 look-ups in flight at a time: more only costs registers
+        if ((s + 1) % (NIB <= 4 ? 8 : 4) == 0) __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 #pragma unroll
-  for (int s = 0; s < LUT_SPL; ++s) {
-    const uint32_t sub = (blockIdx.x * LUT_SPL + s) * 256 + tid;
+  for (int s = 0; s < SPL; ++s) {
+    const uint32_t sub = (blockIdx.x * SPL + s) * 256 + tid;
     if (sub < n_sub) {
       partial[(int64_t)blockIdx.y * n_sub + sub] = total[s];
-      partial_cnt[(int64_t)blockIdx.y * n_sub + sub] = count_same ? same_cnt[s] : 0u;
+      partial_cnt[(int64_t)blockIdx.y * n_sub + sub] = (s == 0 && count_same) ? same_cnt : 0u;   // only the sum is used
     }
   }
 }
@@ -527,35 +542,41 @@ __global__ __launch_bounds__(256) void score_lut_kernel(const float* __restrict_
 // ------------------------------------------------------------------ reduce + argmin
 __global__ __launch_bounds__(256) void zero_i64_kernel(unsigned long long* p) { *p = 0ull; }
 
-// One workgroup per subset: thread i adds the partial sums of tiles i, i + 256, ... in fp64, then a
-// tree over the 256 threads; the order depends on nothing but the tile count.
+// A workgroup adds the partial sums of SUBS neighbouring subsets: thread (strand, j) adds tiles strand,
+// strand + 256 / SUBS, ... of subset j in fp64, then a tree over the strands; the order depends on nothing but
+// the tile count and SUBS.  SUBS = 1 suits a handful of subsets; with thousands, SUBS = 32 reads the partial
+// sums (subset index fastest) in 128-byte runs.
+template <int SUBS>
 __global__ __launch_bounds__(256) void reduce_kernel(const float* __restrict__ partial,
                                                      const uint32_t* __restrict__ partial_cnt,
                                                      int64_t n_tiles, uint32_t n_sub,
                                                      float* __restrict__ loss,
                                                      unsigned long long* unaffected) {
+  constexpr int STRANDS = 256 / SUBS;
   __shared__ double ss[256];
   __shared__ unsigned long long sc[256];
-  const uint32_t sub = blockIdx.x;
+  const int j = threadIdx.x % SUBS, strand = threadIdx.x / SUBS;
+  const uint32_t sub = blockIdx.x * SUBS + j;
   double s = 0.0;
   unsigned long long c = 0;
-  for (int64_t i = threadIdx.x; i < n_tiles; i += 256) {
-    s += (double)partial[i * n_sub + sub];
-    c += partial_cnt[i * n_sub + sub];
-  }
+  if (sub < n_sub)
+    for (int64_t i = strand; i < n_tiles; i += STRANDS) {
+      s += (double)partial[i * n_sub + sub];
+      c += partial_cnt[i * n_sub + sub];
+    }
   ss[threadIdx.x] = s;
   sc[threadIdx.x] = c;
   __syncthreads();
-  for (int off = 128; off >= 1; off >>= 1) {
-    if ((int)threadIdx.x < off) {
-      ss[threadIdx.x] += ss[threadIdx.x + off];
-      sc[threadIdx.x] += sc[threadIdx.x + off];
+  for (int off = STRANDS / 2; off >= 1; off >>= 1) {
+    if (strand < off) {
+      ss[threadIdx.x] += ss[threadIdx.x + off * SUBS];
+      sc[threadIdx.x] += sc[threadIdx.x + off * SUBS];
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    loss[sub] = (float)ss[0];
-    if (unaffected && sc[0]) atomicAdd(unaffected, sc[0]);   // integer: order does not matter
+  if (strand == 0 && sub < n_sub) {
+    loss[sub] = (float)ss[threadIdx.x];
+    if (unaffected && sc[threadIdx.x]) atomicAdd(unaffected, sc[threadIdx.x]);   // integer: order does not matter
   }
 }
 
@@ -623,25 +644,46 @@ int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
   const int64_t n_combo = binomial(p->n_act, p->kk);
   p->n_combo = (int)(n_combo < (1 << 20) ? n_combo : (1 << 20));
   p->use_lut = p->n_sub >= 512 && p->n_act <= LUT_MAX_ACT && n_combo <= LUT_MAX_COMBO;
-  // Aim for a few thousand scoring workgroups; tiles of 32..256 tokens.
-  const int64_t sub_blocks = p->use_lut ? ceil_div(p->n_sub, 256 * LUT_SPL) : ceil_div(p->n_sub, score_threads(p->n_sub));
-  int tile = 256;
-  // (the table scorer's workgroups carry 2048 subsets each and re-read the pattern table per workgroup: fewer, longer ones)
-  const int64_t want_blocks = p->use_lut ? 1024 : 4096;
-  while (tile > 32 && sub_blocks * ceil_div(T, tile) < want_blocks) tile >>= 1;
-  p->tok_tile = tile;
-  p->n_tok_tiles = ceil_div(T, tile);
-  if (p->n_tok_tiles > 65535) { p->tok_tile = (int)ceil_div(T, 65535); p->n_tok_tiles = ceil_div(T, p->tok_tile); }
+  p->lut_spl = 0;
+  if (p->use_lut) {
+    // Subsets per lane: the choice that leaves the fewest idle slots in the last workgroup of 256 lanes, among those
+    // whose look-up addresses (one per subset and mask nibble, the same for every token) fit the register file.
+    int64_t best = 0;
+    for (int spl : {8, 17}) {
+      if (spl > 8 && spl * ((E + 3) / 4) > LUT_MAX_ADDR) continue;
+      const int64_t slots = ceil_div(p->n_sub, 256 * spl) * spl;
+      if (!p->lut_spl || slots < best) { p->lut_spl = spl; best = slots; }
+    }
+    // Workgroups of equal length, about as many as a 256-CU part holds at once (three per CU by their LDS): tiles
+    // of whole token groups, 32 to 1024 tokens.
+    const int64_t sub_blocks = ceil_div(p->n_sub, 256 * p->lut_spl);
+    const int64_t want_tiles = sub_blocks < 768 ? 768 / sub_blocks : 1;
+    int64_t tile = ceil_div(ceil_div(T, want_tiles), LUT_TG) * LUT_TG;
+    tile = tile < 32 ? 32 : tile > 1024 ? 1024 : tile;
+    p->tok_tile = (int)tile;
+  } else {
+    // Aim for a few thousand scoring workgroups; tiles of 32..256 tokens.
+    const int64_t sub_blocks = ceil_div(p->n_sub, score_threads(p->n_sub));
+    int tile = 256;
+    while (tile > 32 && sub_blocks * ceil_div(T, tile) < 4096) tile >>= 1;
+    p->tok_tile = tile;
+  }
+  p->n_tok_tiles = ceil_div(T, p->tok_tile);
+  if (p->n_tok_tiles > 65535) {                          // the grid's second dimension
+    p->tok_tile = (int)(ceil_div(ceil_div(T, 65535), LUT_TG) * LUT_TG);
+    p->n_tok_tiles = ceil_div(T, p->tok_tile);
+  }
   size_t off = 0;
   p->off_gram = off; off += align256((size_t)T * E * E * sizeof(float));
   p->off_rec = off; off += align256((size_t)T * p->rec_floats * sizeof(float));
   p->off_masks = off;
   p->off_partial = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(float));
   p->off_partial_cnt = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(uint32_t));
-  p->off_qtab = p->off_sel = off;
+  p->off_qtab = p->off_sel = p->off_nib = off;
   if (p->use_lut) {
     p->off_qtab = off; off += align256((size_t)T * p->n_combo * sizeof(float));
     p->off_sel = off; off += align256(((size_t)1 << p->n_act) * sizeof(uint16_t));
+    p->off_nib = off; off += align256((size_t)((T + 1) / 2) * ((E + 3) / 4) * 16 * sizeof(uint32_t));
   }
   p->total = off > 0 ? off : 256;
   return MOEP_OK;
@@ -718,32 +760,42 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
       float* qtab = (float*)(ws + p.off_qtab);
       uint16_t* sel = (uint16_t*)(ws + p.off_sel);
       hipLaunchKernelGGL(selidx_kernel, dim3((unsigned)ceil_div((int64_t)1 << p.n_act, 256)), dim3(256), 0, s, p.n_act, p.kk, sel);
+      uint16_t* nibtab = (uint16_t*)(ws + p.off_nib);
+      const int nib = (p.E + 3) / 4;
       const dim3 qgrid((unsigned)p.T), qblock(p.n_combo <= 64 ? 64 : 256);
 #define MOEP_QTABLE_CASE(C)                                                                                       \
   case C:                                                                                                         \
     if (p.n_act == C)                                                                                             \
-      hipLaunchKernelGGL((qtable_kernel<C, true>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo, qtab); \
+      hipLaunchKernelGGL((qtable_kernel<C, true>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo, qtab, \
+                         nib, nibtab);                                                                            \
     else                                                                                                          \
-      hipLaunchKernelGGL((qtable_kernel<C, false>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo, qtab); \
+      hipLaunchKernelGGL((qtable_kernel<C, false>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo,      \
+                         qtab, nib, nibtab);                                                                      \
     break;
       switch (cap) {
         MOEP_QTABLE_CASE(2) MOEP_QTABLE_CASE(4) MOEP_QTABLE_CASE(6) MOEP_QTABLE_CASE(8) MOEP_QTABLE_CASE(12)
         default: return fail(MOEP_EUNSUPPORTED, "prune_enumerate: no selection table for %d active ranks", p.n_act);
       }
 #undef MOEP_QTABLE_CASE
-      const dim3 grid((unsigned)ceil_div(p.n_sub, 256 * LUT_SPL), (unsigned)p.n_tok_tiles);
-      const int ord_off = rec_order_off(cap);
+      const dim3 grid((unsigned)ceil_div(p.n_sub, 256 * p.lut_spl), (unsigned)p.n_tok_tiles);
       const bool count_same = p.kk == p.k;
-#define MOEP_LUT_CASE(N)                                                                                          \
-  case N:                                                                                                         \
-    hipLaunchKernelGGL(score_lut_kernel<N>, grid, dim3(256), 0, s, rec, qtab, sel, p.T, p.tok_tile, p.E, p.r,     \
-                       p.n_act, p.n_combo, p.rec_floats, ord_off, count_same, (uint32_t)p.n_sub, partial, pcnt);   \
-    break;
-      switch ((p.E + 3) / 4) {
-        MOEP_LUT_CASE(1) MOEP_LUT_CASE(2) MOEP_LUT_CASE(3) MOEP_LUT_CASE(4)
-        MOEP_LUT_CASE(5) MOEP_LUT_CASE(6) MOEP_LUT_CASE(7) MOEP_LUT_CASE(8)
+#define MOEP_LUT_LAUNCH(N, S)                                                                                     \
+  hipLaunchKernelGGL((score_lut_kernel<N, S>), grid, dim3(256), 0, s, qtab, (const uint32_t*)nibtab, sel, p.T, p.tok_tile, p.E,    \
+                     p.r, p.n_act, p.n_combo, count_same, (uint32_t)p.n_sub, partial, pcnt)
+      // 512 subsets or more with at most 12 active ranks: 12 experts at least, three nibbles
+      switch (nib * 100 + p.lut_spl) {
+        case 308: MOEP_LUT_LAUNCH(3, 8); break;
+        case 408: MOEP_LUT_LAUNCH(4, 8); break;
+        case 417: MOEP_LUT_LAUNCH(4, 17); break;         // (up to 12 experts never have the subsets for it)
+        case 508: MOEP_LUT_LAUNCH(5, 8); break;
+        case 608: MOEP_LUT_LAUNCH(6, 8); break;
+        case 708: MOEP_LUT_LAUNCH(7, 8); break;
+        case 808: MOEP_LUT_LAUNCH(8, 8); break;
+        default:
+          return fail(MOEP_EUNSUPPORTED, "prune_enumerate: no table scorer for %d experts, %d subsets per lane", p.E,
+                      p.lut_spl);
       }
-#undef MOEP_LUT_CASE
+#undef MOEP_LUT_LAUNCH
       MOEP_HIP(hipGetLastError());
     } else {
       Timed t("subset_score", s);
@@ -763,8 +815,13 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
   {
     Timed t("loss_reduce_argmin", s);
     if (unaffected) hipLaunchKernelGGL(zero_i64_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)unaffected);
-    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)p.n_sub), dim3(256), 0, s, partial, pcnt,
-                       p.T > 0 ? p.n_tok_tiles : 0, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
+    const int64_t red_tiles = p.T > 0 ? p.n_tok_tiles : 0;
+    if (p.n_sub >= 1024)
+      hipLaunchKernelGGL(reduce_kernel<32>, dim3((unsigned)ceil_div(p.n_sub, 32)), dim3(256), 0, s, partial, pcnt,
+                         red_tiles, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
+    else
+      hipLaunchKernelGGL(reduce_kernel<1>, dim3((unsigned)p.n_sub), dim3(256), 0, s, partial, pcnt,
+                         red_tiles, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
     hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, s, loss, (uint32_t)p.n_sub, p.E, p.r, argmin, argmin_mask);
     MOEP_HIP(hipGetLastError());
   }

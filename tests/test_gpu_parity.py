@@ -87,7 +87,9 @@ ENUM_CASES = [
     (20, 2, 17, 60, 64, "bf16"),      # 1140 subsets, 5 nibbles
     (12, 1, 6, 70, 64, "bf16"),       # top-1: 924 subsets, 7 selections per token
     (12, 3, 6, 300, 64, "f32"),       # 924 subsets, 84 selections, several token groups and a ragged last one
-    (16, 4, 8, 517, 64, "bf16"),      # 12870 subsets over several token tiles
+    (16, 4, 8, 517, 64, "bf16"),      # 12870 subsets over several token tiles, 17 subsets per lane
+    (16, 3, 7, 39, 64, "bf16"),       # 11440 subsets, 8 per lane; the last token group holds 7 tokens
+    (15, 2, 11, 2049, 64, "bf16"),    # 1365 subsets, tiles of 32 tokens, the last one a single token
 ]
 
 

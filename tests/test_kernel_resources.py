@@ -25,3 +25,14 @@ def test_packed_gemm_instantiations_do_not_spill(gemm_usage):
 def test_pack_kernel_is_light(gemm_usage):
     pack = [u for n, u in gemm_usage.items() if "pack_kernel" in n]
     assert pack and all(u["ScratchSize"] == 0 for u in pack)
+
+
+def test_table_scorer_keeps_three_wavefronts_per_simd_without_spilling():
+    """The look-up scorer is planned as one resident round of workgroups, three per CU: every instantiation has to
+    fit three wavefronts per SIMD with its per-subset look-up addresses in registers, not in scratch memory."""
+    usage = build.kernel_resource_usage("enumerate.hip")
+    luts = {n: u for n, u in usage.items() if "score_lut_kernel" in n}
+    assert len(luts) >= 7
+    for name, u in luts.items():
+        assert u["ScratchSize"] == 0 and u["VGPRs Spill"] == 0, (name, u)
+        assert u["Occupancy"] >= 3, (name, u)
