@@ -469,6 +469,11 @@ __global__ __launch_bounds__(256) void qtable_kernel(const float* __restrict__ r
 // one look-up per nibble of the kept mask (lanes of a wavefront hold neighbouring subsets: few distinct entries, no
 // bank conflicts), one of the pattern's selection index, one of that selection's error.
 constexpr int LUT_TG = 8, LUT_MAX_ACT = 12, LUT_MAX_COMBO = 512, LUT_MAX_ADDR = 68;
+// Where the pattern table keeps pattern `pat` in LDS: pattern bits 6..10 folded onto the bits that choose the bank.
+// The patterns of a wavefront's 64 subsets differ in the few rank positions of the experts that vary among them, any
+// of the n_act; left to bits 1..5 alone the bank would ignore the rest and they would queue on a few banks.
+__device__ __forceinline__ uint32_t lut_swizzle(uint32_t pat) { return pat ^ ((pat >> 5) & 0x3eu); }
+
 template <int NIB, int SPL>    // NIB = nibbles of the kept mask: ceil(E / 4)
 __global__ __launch_bounds__(256, 3) void score_lut_kernel(const float* __restrict__ qtab,
                                                         const uint32_t* __restrict__ nibtab,
@@ -481,7 +486,7 @@ __global__ __launch_bounds__(256, 3) void score_lut_kernel(const float* __restri
   __shared__ uint32_t s_nib[2][LUT_TG / 2 * NT];
   __shared__ float s_q[2][LUT_TG * LUT_MAX_COMBO];
   const int tid = threadIdx.x;
-  for (int i = tid; i < (1 << n_act); i += 256) s_sel[i] = sel[i];
+  for (int i = tid; i < (1 << n_act); i += 256) s_sel[lut_swizzle((uint32_t)i)] = sel[i];
   uint32_t mask[SPL];
   float total[SPL];
   uint32_t same_cnt = 0;                                 // over all of the lane's subsets
@@ -516,11 +521,11 @@ __global__ __launch_bounds__(256, 3) void score_lut_kernel(const float* __restri
         uint32_t pat = 0;                                // low half: token tk, high half: token tk + 1
 #pragma unroll
         for (int nb = 0; nb < NIB; ++nb) pat |= nib[nb * 16 + ((mask[s] >> (4 * nb)) & 15u)];
-        const uint32_t si0 = s_sel[pat & 0xffffu];
+        const uint32_t si0 = s_sel[lut_swizzle(pat & 0xffffu)];
         total[s] += qrow[si0];
         same_cnt += si0 == 0 ? 1u : 0u;
         if (pair) {
-          const uint32_t si1 = s_sel[pat >> 16];
+          const uint32_t si1 = s_sel[lut_swizzle(pat >> 16)];
           total[s] += qrow[n_combo + si1];
           same_cnt += si1 == 0 ? 1u : 0u;
         }
