@@ -275,6 +275,24 @@ def test_planted_argmin():
     assert l2[i14] > 0.0
 
 
+def test_argmin_is_the_lowest_index_among_equal_losses():
+    # Keeping five experts of six when two are never routed to: the two subsets that drop one of those two both
+    # reproduce the layer exactly; the one that comes first in lexicographic order is the argmin.
+    logits, Y = enumeration_case(11, T=40, E=6, H=4)
+    logits[:, [1, 4]] = -1e9
+    loss, amin, _ = oracle.prune_enumerate(logits, Y, 2, 5)
+    subsets = oracle.kept_subsets(6, 5)
+    first, second = subsets.index((0, 1, 2, 3, 5)), subsets.index((0, 2, 3, 4, 5))
+    assert first < second and loss[first] == 0.0 and loss[second] == 0.0
+    assert np.all(np.delete(loss, [first, second]) > 0.0)
+    assert amin == first
+    # expert outputs that are all zero: every loss is exactly 0 and the argmin is subset 0
+    loss0, amin0, _ = oracle.prune_enumerate(logits, np.zeros_like(Y), 2, 3)
+    assert not loss0.any() and amin0 == 0
+    gram, gram_amin, _ = oracle.prune_enumerate_gram_form(logits, Y, 2, 5)
+    assert gram_amin == first and gram[first] == 0.0 and gram[second] == 0.0
+
+
 def test_r_smaller_than_k_uses_all_kept():
     logits, Y = enumeration_case(10, T=12, E=4, H=3)
     loss, _, _ = oracle.prune_enumerate(logits, Y, k=3, r=1)
