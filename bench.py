@@ -348,6 +348,36 @@ def main():
             "kernels_ms": {n: v[0] / v[1] for n, v in sorted(rk_timing.items())},
         }
         del ws_rk, rk_out
+    if all(math.comb(E, r) <= 128 for r in cfg.rs) and k <= 4 and E * H * 2 <= 148 * 1024:
+        # Extra leg, NOT part of `value`: Eq. 3 as written (no Gram matrices; every token's rows read once and kept in
+        # LDS while all subsets are scored) against the Gram path, each r on its own, same logits and Y.
+        ws_dir = torch.empty(max(binding._lib.prune_enumerate_direct_workspace(T, E, H, k, r, dt) for r in cfg.rs),
+                             dtype=torch.uint8, device=dev)
+        leg = {}
+        for r in cfg.rs:
+            d = pkg.prune_enumerate_direct(logits_b, Y, k, r, workspace=ws_dir)
+            g = pkg.prune_enumerate(logits_b, Y, k, r, workspace=ws_enum)
+            torch.cuda.synchronize()
+            pkg.kernel_timing_enable(True)
+            pkg.kernel_timing_reset()
+            for _ in range(3):
+                pkg.prune_enumerate_direct(logits_b, Y, k, r, workspace=ws_dir)
+                pkg.prune_enumerate(logits_b, Y, k, r, workspace=ws_enum)
+            torch.cuda.synchronize()
+            tm = pkg.kernel_timing_collect()
+            pkg.kernel_timing_enable(False)
+            direct_ms = tm["direct_gather_weight_reduce"][0] / tm["direct_gather_weight_reduce"][1]
+            gram_ms = sum(tm[n][0] / tm[n][1] for n in ("gram", "routing_prep", "subset_score", "subset_score_tables")
+                          if n in tm)
+            leg[f"r={r}"] = {"direct_ms": direct_ms, "gram_path_ms": gram_ms,
+                             "bytes_of_Y": float(E) * T * H * es,
+                             "direct_GBps": float(E) * T * H * es / (direct_ms * 1e-3) / 1e9,
+                             "max_rel_difference": float(((d[0] - g[0]).abs() / g[0].abs().clamp_min(1e-30)).max().item()),
+                             "same_argmin": int(d[1].item()) == int(g[1].item())}
+        leg["all_r"] = {"direct_ms": sum(v["direct_ms"] for v in leg.values()),
+                        "gram_path_ms_one_shared_gram_pass": enum_ms}
+        out["direct_path"] = leg
+        del ws_dir
     if args.workload == "C3":
         # The paper's own figures for this path, as context only: other hardware, the whole 32-layer model, and its wall
         # times include the calibration forward (Sec. 4.1 for the pruning times, the speed-up table of Sec. 4 for skipping).

@@ -124,6 +124,22 @@ int prune_enumerate_multi(const float* logits, const void* Y, int64_t T, int E, 
                           uint32_t* argmin_mask, int64_t* unaffected_pairs, void* ws, size_t ws_bytes,
                           void* hip_stream);
 
+/* ---- prune_enumerate_direct -------------------------------------------------- */
+/* Sec. 3.2, Eq. 3 evaluated as it is written: arguments, outputs and conventions of prune_enumerate,
+ * but F'(x_t, C) - F(x_t) = sum_e d_e E_e(x_t) is formed over the hidden units for every (subset,
+ * token) pair whose routing changes (d = Eq. 1 weights of the pruned routing minus those of the full
+ * routing, at most 2k experts) and its squares are summed; no Gram matrices.  Each token's E rows of Y
+ * are read from memory once and kept in LDS while all subsets are scored, so the pass moves the bytes
+ * of the Gram pass and does O(k H) arithmetic per pair instead of O(k^2).  Kept as the measured
+ * alternative to the Gram path and as a cross-check on it with different arithmetic.
+ *   - Limits (MOEP_EUNSUPPORTED beyond them): C(E,r) <= 128, k <= 4, H a multiple of 8 (bf16) or
+ *     4 (fp32), E*H*sizeof(dt) + 11 KB within the 160 KB of LDS.
+ *   - The losses agree with prune_enumerate's to fp32 rounding, not bit for bit. */
+size_t prune_enumerate_direct_workspace(int64_t T, int E, int H, int k, int r, moep_dtype dt);
+int prune_enumerate_direct(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt,
+                           int k, int r, float* loss, int32_t* argmin, uint32_t* argmin_mask,
+                           int64_t* unaffected_pairs, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- prune_enumerate_static -------------------------------------------------- */
 /* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc: prune_enumerate with no workspace argument.  The scratch

@@ -7,7 +7,7 @@ not been built -- there is no CPU fallback.  `workloads` only draws seeded
 synthetic inputs and can be imported on its own.
 """
 _BINDING_NAMES = (
-    "moe_expert_outputs", "prune_enumerate", "prune_enumerate_multi", "prune_enumerate_static",
+    "moe_expert_outputs", "prune_enumerate", "prune_enumerate_multi", "prune_enumerate_static", "prune_enumerate_direct",
     "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_pack_weights", "moe_forward_pruned_skip_packed", "moe_expert_outputs_packed",
     "moe_forward_skip_topk", "skip_calibrate_beta", "expert_selection_stats",

@@ -25,6 +25,7 @@ EXPORTS = (
     "moe_expert_outputs_workspace", "moe_expert_outputs",
     "prune_enumerate_workspace", "prune_enumerate",
     "prune_enumerate_multi_workspace", "prune_enumerate_multi", "prune_enumerate_static",
+    "prune_enumerate_direct_workspace", "prune_enumerate_direct",
     "moe_forward_skip_workspace", "moe_forward_skip", "moe_forward_pruned_skip",
     "moe_packed_weights_bytes", "moe_pack_weights", "moe_forward_pruned_skip_packed",
     "moe_expert_outputs_packed_workspace", "moe_expert_outputs_packed",
@@ -69,6 +70,10 @@ def _load() -> ctypes.CDLL:
     lib.prune_enumerate.restype = c_int
     lib.prune_enumerate.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
                                     c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.prune_enumerate_direct_workspace.restype = c_size_t
+    lib.prune_enumerate_direct_workspace.argtypes = [c_int64, c_int, c_int, c_int, c_int, c_int]
+    lib.prune_enumerate_direct.restype = c_int
+    lib.prune_enumerate_direct.argtypes = lib.prune_enumerate.argtypes
     lib.prune_enumerate_static.restype = c_int
     lib.prune_enumerate_static.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
                                            c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -239,6 +244,26 @@ def prune_enumerate(logits, Y, k: int, r: int, workspace=None, count_unaffected:
     ws = _workspace(need, dev, workspace)
     _check(_lib.prune_enumerate(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
                                 _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
+    return loss, argmin, amask, unaffected
+
+
+def prune_enumerate_direct(logits, Y, k: int, r: int, workspace=None, count_unaffected: bool = True):
+    """prune_enumerate's outputs from Eq. 3 as written (no Gram matrices); at most 128 subsets, k <= 4."""
+    dev = _dev(logits, Y)
+    dt = _dtype_code(Y)
+    E, T, H = Y.shape
+    assert logits.shape == (T, E) and logits.dtype == torch.float32
+    n = num_subsets(E, r)
+    if n < 0:
+        raise MoepError(1, f"r={r} out of range [1, E={E}]")
+    loss = torch.empty((n,), dtype=torch.float32, device=dev)
+    argmin = torch.empty((1,), dtype=torch.int32, device=dev)
+    amask = torch.empty((1,), dtype=torch.int32, device=dev)
+    unaffected = torch.empty((1,), dtype=torch.int64, device=dev) if count_unaffected else None
+    need = _lib.prune_enumerate_direct_workspace(T, E, H, k, r, dt)
+    ws = _workspace(need, dev, workspace)
+    _check(_lib.prune_enumerate_direct(_ptr(logits), _ptr(Y), T, E, H, dt, k, r, _ptr(loss), _ptr(argmin),
+                                       _ptr(amask), _ptr(unaffected), _ptr(ws), ws.numel(), _stream(dev)))
     return loss, argmin, amask, unaffected
 
 

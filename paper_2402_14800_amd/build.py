@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoeprune.so")
-SOURCES = ["api.hip", "router.hip", "gemm_bf16_packed.hip", "gemm_f32.hip", "enumerate.hip", "skip.hip", "calibrate.hip", "stats.hip", "no_alloc.hip", "mfma_ceiling.hip"]
+SOURCES = ["api.hip", "router.hip", "gemm_bf16_packed.hip", "gemm_f32.hip", "enumerate.hip", "enumerate_direct.hip", "skip.hip", "calibrate.hip", "stats.hip", "no_alloc.hip", "mfma_ceiling.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

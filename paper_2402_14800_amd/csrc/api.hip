@@ -358,6 +358,28 @@ int prune_enumerate(const float* logits, const void* Y, int64_t T, int E, int H,
                           (char*)ws, (hipStream_t)hip_stream);
 }
 
+// Eq. 3 as written (no Gram matrices): the alternative the Gram path is measured against.
+size_t prune_enumerate_direct_workspace(int64_t T, int E, int H, int k, int r, moep_dtype dt) {
+  if (!valid_shape(T, E, H, 1, dt, "prune_enumerate_direct_workspace")) return 0;
+  DirectPlan p;
+  if (plan_enumerate_direct(T, E, H, k, r, dt, &p)) return 0;
+  return p.total;
+}
+
+int prune_enumerate_direct(const float* logits, const void* Y, int64_t T, int E, int H, moep_dtype dt, int k, int r,
+                           float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected_pairs, void* ws,
+                           size_t ws_bytes, void* hip_stream) {
+  const char* who = "prune_enumerate_direct";
+  if (!valid_shape(T, E, H, 1, dt, who)) return MOEP_EINVAL;
+  DirectPlan p;
+  if (int st = plan_enumerate_direct(T, E, H, k, r, dt, &p)) return st;
+  if (!loss || !argmin || !argmin_mask) return fail(MOEP_EINVAL, "%s: NULL loss, argmin or argmin_mask", who);
+  if (T > 0 && (!logits || !Y)) return fail(MOEP_EINVAL, "%s: NULL logits or Y", who);
+  if (int st = check_ws(ws, ws_bytes, p.total, who)) return st;
+  return launch_enumerate_direct(p, logits, Y, dt, loss, argmin, argmin_mask, unaffected_pairs, (char*)ws,
+                                 (hipStream_t)hip_stream);
+}
+
 // Several r on the same logits and Y: the Gram pass, which does not depend on r, runs once.
 size_t prune_enumerate_multi_workspace(int64_t T, int E, int H, int k, int n_r, const int* rs, moep_dtype dt) {
   if (!valid_shape(T, E, H, 1, dt, "prune_enumerate_multi_workspace") || n_r < 1 || !rs) return 0;

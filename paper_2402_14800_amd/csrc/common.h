@@ -151,6 +151,26 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
                      float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
                      char* ws, hipStream_t s, const RankedSource* ranked = nullptr, bool reuse_gram = false);
 
+// fp64 sum of n_tiles partial sums per subset (partial[tile * n_sub + subset]) in a fixed order -> loss; sum of the
+// partial counts -> *unaffected (may be NULL); lowest-index argmin and its kept mask
+int launch_reduce_argmin(const float* partial, const uint32_t* partial_cnt, int64_t n_tiles, int64_t n_sub, int E,
+                         int r, float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected,
+                         hipStream_t s);
+// masks[i] = kept mask of subset i
+int launch_subset_masks(int E, int r, int64_t n_sub, uint32_t* masks, hipStream_t s);
+
+// The same losses straight from the definition, without Gram matrices (enumerate_direct.hip).
+struct DirectPlan {
+  int64_t T; int E, H, k, r;
+  int64_t n_sub;
+  int blocks;        // workgroups, each walking tokens b, b + blocks, ...
+  size_t lds_bytes;  // dynamic LDS per workgroup
+  size_t off_masks, off_partial, off_partial_cnt, total;
+};
+int plan_enumerate_direct(int64_t T, int E, int H, int k, int r, moep_dtype dt, DirectPlan* p);
+int launch_enumerate_direct(const DirectPlan& p, const float* logits, const void* Y, moep_dtype dt, float* loss,
+                            int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected, char* ws, hipStream_t s);
+
 // ---- skipping ---------------------------------------------------------------------
 struct SkipPlan {
   int64_t T; int E, H, F;

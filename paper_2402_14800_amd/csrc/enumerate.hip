@@ -56,6 +56,11 @@ __device__ uint32_t unrank_device(int E, int r, uint32_t idx) {
   return mask;
 }
 
+__global__ __launch_bounds__(256) void masks_kernel(int E, int r, uint32_t n_sub, uint32_t* __restrict__ masks) {
+  const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_sub) masks[i] = unrank_device(E, r, i);
+}
+
 // ------------------------------------------------------------------ Gram, bf16 (MFMA)
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -817,19 +822,28 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
       MOEP_HIP(hipGetLastError());
     }
   }
-  {
-    Timed t("loss_reduce_argmin", s);
-    if (unaffected) hipLaunchKernelGGL(zero_i64_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)unaffected);
-    const int64_t red_tiles = p.T > 0 ? p.n_tok_tiles : 0;
-    if (p.n_sub >= 1024)
-      hipLaunchKernelGGL(reduce_kernel<32>, dim3((unsigned)ceil_div(p.n_sub, 32)), dim3(256), 0, s, partial, pcnt,
-                         red_tiles, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
-    else
-      hipLaunchKernelGGL(reduce_kernel<1>, dim3((unsigned)p.n_sub), dim3(256), 0, s, partial, pcnt,
-                         red_tiles, (uint32_t)p.n_sub, loss, (unsigned long long*)unaffected);
-    hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, s, loss, (uint32_t)p.n_sub, p.E, p.r, argmin, argmin_mask);
-    MOEP_HIP(hipGetLastError());
-  }
+  return launch_reduce_argmin(partial, pcnt, p.T > 0 ? p.n_tok_tiles : 0, p.n_sub, p.E, p.r, loss, argmin, argmin_mask,
+                              unaffected, s);
+}
+
+int launch_reduce_argmin(const float* partial, const uint32_t* pcnt, int64_t n_tiles, int64_t n_sub, int E, int r,
+                         float* loss, int32_t* argmin, uint32_t* argmin_mask, int64_t* unaffected, hipStream_t s) {
+  Timed t("loss_reduce_argmin", s);
+  if (unaffected) hipLaunchKernelGGL(zero_i64_kernel, dim3(1), dim3(1), 0, s, (unsigned long long*)unaffected);
+  if (n_sub >= 1024)
+    hipLaunchKernelGGL(reduce_kernel<32>, dim3((unsigned)ceil_div(n_sub, 32)), dim3(256), 0, s, partial, pcnt,
+                       n_tiles, (uint32_t)n_sub, loss, (unsigned long long*)unaffected);
+  else
+    hipLaunchKernelGGL(reduce_kernel<1>, dim3((unsigned)n_sub), dim3(256), 0, s, partial, pcnt, n_tiles,
+                       (uint32_t)n_sub, loss, (unsigned long long*)unaffected);
+  hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, s, loss, (uint32_t)n_sub, E, r, argmin, argmin_mask);
+  MOEP_HIP(hipGetLastError());
+  return MOEP_OK;
+}
+
+int launch_subset_masks(int E, int r, int64_t n_sub, uint32_t* masks, hipStream_t s) {
+  hipLaunchKernelGGL(masks_kernel, dim3((unsigned)ceil_div(n_sub, 256)), dim3(256), 0, s, E, r, (uint32_t)n_sub, masks);
+  MOEP_HIP(hipGetLastError());
   return MOEP_OK;
 }
 

@@ -112,6 +112,17 @@ int main() {
     EXPECT(prune_enumerate_multi(fp, p, 16, 8, 64, MOEP_BF16, 2, 2, rs, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EINVAL);
     EXPECT(prune_enumerate_multi(fp, p, 16, 8, 64, MOEP_BF16, 2, 0, rs, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EINVAL);
   }
+  // Eq. 3 as written: its limits are argument errors, found before anything touches the GPU
+  EXPECT(prune_enumerate_direct_workspace(262144, 8, 4096, 2, 4, MOEP_BF16) >= 512u * 70 * 8);
+  EXPECT(prune_enumerate_direct_workspace(262144, 16, 2048, 4, 8, MOEP_BF16) == 0);            // 12870 subsets
+  EXPECT(prune_enumerate_direct(fp, p, 16, 16, 64, MOEP_BF16, 4, 8, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EUNSUPPORTED);
+  EXPECT(prune_enumerate_direct(fp, p, 16, 16, 64, MOEP_BF16, 5, 15, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EUNSUPPORTED);
+  EXPECT(prune_enumerate_direct(fp, p, 16, 8, 16384, MOEP_BF16, 2, 6, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EUNSUPPORTED);
+  EXPECT(prune_enumerate_direct(fp, p, 16, 8, 70, MOEP_F32, 2, 6, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EUNSUPPORTED);
+  EXPECT(prune_enumerate_direct(fp, p, 16, 8, 64, MOEP_BF16, 2, 9, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EINVAL);
+  EXPECT(prune_enumerate_direct(fp, p, 16, 8, 64, MOEP_BF16, 2, 6, nullptr, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EINVAL);
+  EXPECT(prune_enumerate_direct(fp, nullptr, 16, 8, 64, MOEP_BF16, 2, 6, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EINVAL);
+  EXPECT(prune_enumerate_direct(fp, p, 16, 8, 64, MOEP_BF16, 2, 6, fp, ip, up, nullptr, p, 16, nullptr) == MOEP_EWORKSPACE);
   EXPECT(prune_enumerate_static(fp, p, 200000, 8, 64, MOEP_BF16, 2, 4, fp, ip, up, nullptr, nullptr) == MOEP_EWORKSPACE);
   EXPECT(prune_enumerate_static(fp, p, 100, 8, 64, MOEP_BF16, 2, 4, nullptr, ip, up, nullptr, nullptr) == MOEP_EINVAL);
   EXPECT(prune_enumerate_ranked(fp, ip, ip, p, 16, 8, 64, MOEP_BF16, 4, 2, 4, fp, ip, up, nullptr, p, 1 << 20, nullptr) == MOEP_EINVAL);

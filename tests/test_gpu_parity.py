@@ -170,6 +170,76 @@ def test_prune_enumerate_tables_with_ties_and_logits_far_below_the_maximum():
     assert loss[oracle.kept_subsets(E, 6).index(tuple(low))] > 0.0
 
 
+DIRECT_CASES = [
+    # E, k, r, T, H, dtype -- Eq. 3 as written (no Gram matrices): at most 128 subsets, k <= 4
+    (4, 2, 2, 512, 64, "f32"),
+    (4, 2, 4, 100, 64, "bf16"),       # r = E: nothing changes, every pair counted
+    (4, 3, 2, 77, 128, "bf16"),       # r < k
+    (5, 1, 3, 301, 64, "bf16"),       # top-1
+    (8, 2, 6, 1000, 256, "bf16"),     # more tokens than workgroups: two tokens per workgroup, ragged
+    (8, 2, 4, 1001, 192, "bf16"),     # 70 subsets; 24 chunks of hidden units for 256 threads
+    (8, 2, 7, 333, 100, "f32"),       # H = 100: 25 chunks of 4
+    (8, 4, 5, 130, 4096, "bf16"),     # top-4 (d has up to 8 entries), 64 KB of rows per token, two chunks per thread
+    (9, 3, 7, 50, 320, "bf16"),       # odd E, 40 chunks of hidden units
+    (6, 2, 4, 1, 64, "bf16"),         # a single token
+    (16, 4, 15, 90, 2048, "bf16"),    # 16 experts
+    (32, 2, 31, 40, 128, "f32"),      # 32 experts
+]
+
+
+@pytest.mark.parametrize("E,k,r,T,H,dtype", DIRECT_CASES)
+def test_direct_enumeration_matches_oracle_and_gram_path(E, k, r, T, H, dtype):
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, dtype, seed=2000 + 31 * E + r, device=DEV)
+    loss_t, amin_t, amask_t, unaff_t = pkg.prune_enumerate_direct(logits_t, Y_t, k, r)
+    torch.cuda.synchronize()
+    loss, amin, amask = loss_t.cpu().numpy().astype(np.float64), int(amin_t.item()), int(amask_t.item()) & 0xFFFFFFFF
+    logits, Y = wl.to_f64(logits_t), wl.to_f64(Y_t)
+    ref, _, ref_masks = oracle.prune_enumerate(logits, Y, k, r)
+    check_losses(loss, ref)
+    check_argmin(amin, ref, loss)
+    assert amask == int(ref_masks[amin])
+    assert tie_free(logits)
+    assert int(unaff_t.item()) == (T * math.comb(E - k, r - k) if r >= k else 0)
+    if r == E:
+        assert loss.tolist() == [0.0]
+    # the Gram path on the same inputs: different arithmetic, the same numbers to fp32 rounding
+    gram, gram_amin, _, gram_unaff = run_enumerate(logits_t, Y_t, k, r)
+    np.testing.assert_allclose(loss, gram, rtol=2e-4, atol=0.0)
+    assert gram_unaff == int(unaff_t.item())
+    # reproducible bit for bit
+    again = pkg.prune_enumerate_direct(logits_t, Y_t, k, r)
+    torch.cuda.synchronize()
+    assert torch.equal(again[0], loss_t) and torch.equal(again[1], amin_t)
+
+
+def test_direct_enumeration_limits_empty_batch_and_never_routed_experts():
+    logits_t, Y_t = wl.make_enumeration_inputs(16, 64, 64, "bf16", seed=77, device=DEV)
+    with pytest.raises(pkg.MoepError, match="subsets"):
+        pkg.prune_enumerate_direct(logits_t, Y_t, 4, 8)            # 12870 subsets
+    with pytest.raises(pkg.MoepError, match="k=5"):
+        pkg.prune_enumerate_direct(logits_t, Y_t, 5, 15)
+    big_t = torch.zeros((8, 4, 16384), dtype=torch.bfloat16, device=DEV)      # 256 KB of rows per token
+    with pytest.raises(pkg.MoepError, match="LDS"):
+        pkg.prune_enumerate_direct(torch.zeros((4, 8), device=DEV), big_t, 2, 6)
+    logits_t, Y_t = wl.make_enumeration_inputs(8, 50, 72, "f32", seed=78, device=DEV)
+    with pytest.raises(pkg.MoepError):
+        pkg.prune_enumerate_direct(logits_t, Y_t[:, :, :70].contiguous(), 2, 6)   # H = 70 is no multiple of 4
+    loss, amin, amask, unaff = pkg.prune_enumerate_direct(logits_t[:0].contiguous(), Y_t[:, :0].contiguous(), 2, 6)
+    torch.cuda.synchronize()
+    assert loss.tolist() == [0.0] * 28 and amin.item() == 0 and amask.item() == 0b111111 and unaff.item() == 0
+    # experts 1 and 4 never routed to (Eq. 1 on logits of -1e9): the subset without them costs exactly nothing
+    E, T, H = 6, 200, 64
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, "bf16", seed=9, device=DEV)
+    logits_t[:, [1, 4]] = -1e9
+    loss, amin, amask, _ = pkg.prune_enumerate_direct(logits_t, Y_t, 2, 4)
+    ref, ref_amin, _ = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), 2, 4)
+    assert amin.item() == ref_amin and amask.item() == 0b101101 and loss[ref_amin].item() == 0.0
+    check_losses(loss.cpu().numpy().astype(np.float64), ref)
+    l2, _, _, _ = pkg.prune_enumerate_direct(logits_t, Y_t, 2, 2)   # both survivors at -1e9: weights (1/2, 1/2)
+    ref2, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t), wl.to_f64(Y_t), 2, 2)
+    check_losses(l2.cpu().numpy().astype(np.float64), ref2)
+
+
 def test_prune_enumerate_relabelling_and_scale():
     E, T, H = 8, 512, 128
     logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, "bf16", seed=11, device=DEV)
@@ -456,6 +526,11 @@ def test_config3_enumeration(config3):
         # reproducible bit for bit
         loss2, amin2, _, _ = run_enumerate(logits_t, Y_t, cfg.k, r)
         assert np.array_equal(loss, loss2) and amin == amin2
+        # Eq. 3 as written, over all 262144 tokens: the same losses from different arithmetic
+        direct = pkg.prune_enumerate_direct(logits_t, Y_t, cfg.k, r)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(direct[0].cpu().numpy().astype(np.float64), loss, rtol=1e-4, atol=0.0)
+        assert int(direct[1].item()) == amin and int(direct[3].item()) == unaff
 
 
 def test_config5_skip_forward_sampled(config3):
