@@ -79,7 +79,17 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // c ^ j: the row-wise writes and the column-wise fragment reads are both free of bank conflicts); the next
 // 16 loads are in flight in registers while the current block of 512 hidden units is multiplied.  The
 // same registers serve as both MFMA operands (B = A^T).
-template <int EPAD, bool RANKED>
+// STREAM: Y is far larger than the caches, so its loads carry the non-temporal hint (measured 6.2 -> 6.8 TB/s at
+// 17 GB and 5.6 -> 6.0 TB/s at 4.3 GB; a Y of a few hundred MB that the down projection has just written is
+// better read with ordinary loads: 6.5 against 5.0 TB/s at 0.27 GB).
+// 16 bytes of Y with the non-temporal hint: a stream read once, not worth a place in the caches.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_streaming(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+template <int EPAD, bool RANKED, bool STREAM>
 __global__ __launch_bounds__(256) void gram_bf16_kernel(const uint4* __restrict__ Y,
                                                         const int32_t* __restrict__ slot_of,
                                                         const int32_t* __restrict__ experts,
@@ -112,7 +122,8 @@ __global__ __launch_bounds__(256) void gram_bf16_kernel(const uint4* __restrict_
   uint4 v[16];
 #define MOEP_GRAM_FETCH(kb)                                                                     \
   _Pragma("unroll") for (int j = 0; j < 16; ++j)                                                \
-    v[j] = (rvalid[j] && (kb) * 64 + lane < chunks) ? rowp[j][(kb) * 64] : make_uint4(0, 0, 0, 0);
+    v[j] = !(rvalid[j] && (kb) * 64 + lane < chunks) ? make_uint4(0, 0, 0, 0)                    \
+           : STREAM ? load_streaming(&rowp[j][(kb) * 64]) : rowp[j][(kb) * 64];
   MOEP_GRAM_FETCH(0)
   for (int kb = 0; kb < nkb; ++kb) {
 #pragma unroll
@@ -726,29 +737,39 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
     if (!reuse_gram) {
       Timed t("gram", s);
       const unsigned per_tok_blocks = (unsigned)ceil_div(p.T, 4);
+      // streaming loads for a Y beyond half a GB
+      const bool stream = (double)p.T * (ranked ? ranked->n_rank : p.E) * p.H * 2.0 >= 512.0 * 1024 * 1024;
+#define MOEP_GRAM_LAUNCH(EPAD, RANKED, GRID, ...)                                                              \
+  do {                                                                                                         \
+    if (stream)                                                                                                \
+      hipLaunchKernelGGL((gram_bf16_kernel<EPAD, RANKED, true>), dim3(GRID), dim3(256), 0, s, __VA_ARGS__);    \
+    else                                                                                                       \
+      hipLaunchKernelGGL((gram_bf16_kernel<EPAD, RANKED, false>), dim3(GRID), dim3(256), 0, s, __VA_ARGS__);   \
+  } while (0)
       if (ranked) {
         const int n = ranked->n_rank;
         if (dt != MOEP_BF16)
           hipLaunchKernelGGL(gram_ranked_f32_kernel, dim3(per_tok_blocks), dim3(256), 0, s, (const float*)Y,
                              ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
         else if (n <= 4)
-          hipLaunchKernelGGL((gram_bf16_kernel<4, true>), dim3((unsigned)ceil_div(p.T, 16)), dim3(256), 0, s,
-                             (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+          MOEP_GRAM_LAUNCH(4, true, (unsigned)ceil_div(p.T, 16), (const uint4*)Y, ranked->slot_of, ranked->experts, G,
+                           p.T, p.E, n, p.H);
         else if (n <= 8)
-          hipLaunchKernelGGL((gram_bf16_kernel<8, true>), dim3((unsigned)ceil_div(p.T, 8)), dim3(256), 0, s,
-                             (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+          MOEP_GRAM_LAUNCH(8, true, (unsigned)ceil_div(p.T, 8), (const uint4*)Y, ranked->slot_of, ranked->experts, G,
+                           p.T, p.E, n, p.H);
         else
-          hipLaunchKernelGGL((gram_bf16_kernel<16, true>), dim3(per_tok_blocks), dim3(256), 0, s,
-                             (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n, p.H);
+          MOEP_GRAM_LAUNCH(16, true, per_tok_blocks, (const uint4*)Y, ranked->slot_of, ranked->experts, G, p.T, p.E, n,
+                           p.H);
       } else if (dt == MOEP_BF16) {
         if (p.E <= 4)
-          hipLaunchKernelGGL((gram_bf16_kernel<4, false>), dim3((unsigned)ceil_div(p.T, 16)), dim3(256), 0, s, (const uint4*)Y, nullptr, nullptr, G, p.T, p.E, 0, p.H);
+          MOEP_GRAM_LAUNCH(4, false, (unsigned)ceil_div(p.T, 16), (const uint4*)Y, nullptr, nullptr, G, p.T, p.E, 0, p.H);
         else if (p.E <= 8)
-          hipLaunchKernelGGL((gram_bf16_kernel<8, false>), dim3((unsigned)ceil_div(p.T, 8)), dim3(256), 0, s, (const uint4*)Y, nullptr, nullptr, G, p.T, p.E, 0, p.H);
+          MOEP_GRAM_LAUNCH(8, false, (unsigned)ceil_div(p.T, 8), (const uint4*)Y, nullptr, nullptr, G, p.T, p.E, 0, p.H);
         else if (p.E <= 16)
-          hipLaunchKernelGGL((gram_bf16_kernel<16, false>), dim3(per_tok_blocks), dim3(256), 0, s, (const uint4*)Y, nullptr, nullptr, G, p.T, p.E, 0, p.H);
+          MOEP_GRAM_LAUNCH(16, false, per_tok_blocks, (const uint4*)Y, nullptr, nullptr, G, p.T, p.E, 0, p.H);
         else
           hipLaunchKernelGGL(gram_bf16_32_kernel, dim3(per_tok_blocks), dim3(256), 0, s, (const uint4*)Y, G, p.T, p.E, p.H);
+#undef MOEP_GRAM_LAUNCH
       } else {
         hipLaunchKernelGGL(gram_f32_kernel, dim3(per_tok_blocks), dim3(256), 0, s, (const float*)Y, G, p.T, p.E, p.H);
       }

@@ -879,6 +879,33 @@ def test_rank_limited_pass_matches_dense_pass_and_oracle(dtype, E, H, F, T, k, r
         assert int(unaff_t.item()) == int(du.item())
 
 
+def test_rank_limited_enumeration_with_streaming_loads():
+    """Above half a GB of expert outputs the Gram kernels read them with non-temporal loads (another instantiation).
+    Ranked rows assembled from a dense random Y: the ranked enumeration has to return the dense one's losses, which
+    the oracle checks at this size in the config 3 and config 4 tests (GPU against GPU here)."""
+    E, T, H, k, r, n = 8, 70001, 1024, 2, 6, 4
+    logits_t, Y_t = wl.make_enumeration_inputs(E, T, H, "bf16", seed=4242, device=DEV)
+    assert Y_t.numel() * 2 >= 512 << 20 and T * n * H * 2 >= 512 << 20
+    experts_t = torch.argsort(logits_t, dim=1, descending=True, stable=True)[:, :n].to(torch.int32).contiguous()
+    perm = torch.randperm(T * n, device=DEV, generator=torch.Generator(device=DEV).manual_seed(7))
+    slot_t = perm.view(T, n).to(torch.int32).contiguous()
+    Yr_t = torch.empty((T * n, H), dtype=torch.bfloat16, device=DEV)
+    tok = torch.arange(T, device=DEV)
+    for j in range(n):
+        Yr_t[slot_t[:, j].long()] = Y_t[experts_t[:, j].long(), tok]
+    dense = pkg.prune_enumerate(logits_t, Y_t, k, r)
+    ranked = pkg.prune_enumerate_ranked(logits_t, experts_t, slot_t, Yr_t, k, r)
+    torch.cuda.synchronize()
+    assert torch.equal(ranked[0].view(torch.int32), dense[0].view(torch.int32))      # the same dot products, bit for bit
+    assert torch.equal(ranked[1], dense[1]) and torch.equal(ranked[3], dense[3])
+    head = 3000                                       # and the oracle on a window of the same inputs
+    ref, _, _ = oracle.prune_enumerate(wl.to_f64(logits_t[:head]), wl.to_f64(Y_t[:, :head]), k, r)
+    part = pkg.prune_enumerate(logits_t[:head].contiguous(), Y_t[:, :head].contiguous(), k, r)
+    rest = pkg.prune_enumerate(logits_t[head:].contiguous(), Y_t[:, head:].contiguous(), k, r)
+    check_losses(part[0].cpu().numpy().astype(np.float64), ref)
+    np.testing.assert_allclose((part[0].double() + rest[0].double()).cpu().numpy(), dense[0].double().cpu().numpy(), rtol=2e-5)
+
+
 def test_rank_limited_pass_argument_checks():
     cfg, layer = small_layer("bf16", 8, 2, 128, 256, 64, index=15)
     d = to_dev(layer)
