@@ -353,7 +353,8 @@ def main():
         # LDS while all subsets are scored) against the Gram path, each r on its own, same logits and Y.
         ws_dir = torch.empty(max(binding._lib.prune_enumerate_direct_workspace(T, E, H, k, r, dt) for r in cfg.rs),
                              dtype=torch.uint8, device=dev)
-        leg = {}
+        leg = {"what": "Eq. 3 as written (prune_enumerate_direct) against the Gram path (prune_enumerate), each r on its "
+                       "own, same logits and Y; not part of `value`"}
         for r in cfg.rs:
             d = pkg.prune_enumerate_direct(logits_b, Y, k, r, workspace=ws_dir)
             g = pkg.prune_enumerate(logits_b, Y, k, r, workspace=ws_enum)
@@ -374,7 +375,7 @@ def main():
                              "direct_GBps": float(E) * T * H * es / (direct_ms * 1e-3) / 1e9,
                              "max_rel_difference": float(((d[0] - g[0]).abs() / g[0].abs().clamp_min(1e-30)).max().item()),
                              "same_argmin": int(d[1].item()) == int(g[1].item())}
-        leg["all_r"] = {"direct_ms": sum(v["direct_ms"] for v in leg.values()),
+        leg["all_r"] = {"direct_ms": sum(v["direct_ms"] for v in leg.values() if isinstance(v, dict)),
                         "gram_path_ms_one_shared_gram_pass": enum_ms}
         out["direct_path"] = leg
         del ws_dir
