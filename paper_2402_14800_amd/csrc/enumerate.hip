@@ -256,13 +256,18 @@ __host__ __device__ constexpr int rec_size(int cap) {
   return (rec_order_off(cap) + (cap + 3) / 4 + 3) & ~3;
 }
 
-template <int EMAX>
+// One thread per token.  STAGED: the thread builds its record in LDS (rec_floats + 1 words apart: no bank conflicts)
+// and the workgroup then writes its tokens' records, which are consecutive in memory, in 16-byte pieces; otherwise
+// (records too large for the LDS) every thread writes its own record word by word.
+template <int EMAX, bool STAGED>
 __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ logits,
                                                    const float* __restrict__ G,
                                                    float* __restrict__ rec, int64_t T, int E,
                                                    int k, int n_act, int cap, int rec_floats) {
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= T) return;
+  extern __shared__ float stage[];
+  const int64_t t0 = (int64_t)blockIdx.x * blockDim.x;
+  const int64_t t = t0 + threadIdx.x;
+  if (t < T) {
   float l[EMAX];
 #pragma unroll
   for (int e = 0; e < EMAX; ++e) l[e] = e < E ? logits[t * E + e] : 0.f;
@@ -276,7 +281,7 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ log
       if (f < E && f != e) c += (l[f] > l[e] || (l[f] == l[e] && f < e)) ? 1 : 0;
     rank[e] = e < E ? c : 255;
   }
-  float* R = rec + t * rec_floats;
+  float* R = STAGED ? stage + threadIdx.x * (rec_floats + 1) : rec + t * rec_floats;
   for (int i = 0; i < rec_floats; ++i) R[i] = 0.f;
   uint32_t* Rord = (uint32_t*)(R + rec_order_off(cap));
   int ord[EMAX];
@@ -309,6 +314,17 @@ __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ log
       if (j < n_act) packed |= (uint32_t)ord[j] << (8 * b);
     }
     Rord[w] = packed;
+  }
+  }
+  if (STAGED) {
+    __syncthreads();
+    const int64_t left = T - t0;
+    const int words = (int)(left < (int64_t)blockDim.x ? left : (int64_t)blockDim.x) * rec_floats;   // a multiple of 4
+    float4* dst = (float4*)(rec + t0 * rec_floats);
+    for (int q = 4 * threadIdx.x; q < words; q += 4 * blockDim.x) {
+      const float* src = stage + (q / rec_floats) * (rec_floats + 1) + q % rec_floats;   // the 4 words are one token's
+      dst[q >> 2] = make_float4(src[0], src[1], src[2], src[3]);
+    }
   }
 }
 
@@ -777,13 +793,26 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
     }
     {
       Timed t("routing_prep", s);
-      const dim3 grid((unsigned)ceil_div(p.T, 256));
-      if (p.E <= 8)
-        hipLaunchKernelGGL(prep_kernel<8>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
-      else if (p.E <= 16)
-        hipLaunchKernelGGL(prep_kernel<16>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
-      else
-        hipLaunchKernelGGL(prep_kernel<32>, grid, dim3(256), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act, cap, p.rec_floats);
+      // threads (= tokens) per workgroup: as many as fit 64 KB of LDS with their records, 64 at least
+      int tpb = 256;
+      while (tpb > 64 && (size_t)(p.rec_floats + 1) * tpb * sizeof(float) > 64 * 1024) tpb >>= 1;
+      const size_t lds = (size_t)(p.rec_floats + 1) * tpb * sizeof(float);
+      const bool staged = lds <= 64 * 1024;
+      if (!staged) tpb = 256;
+      const dim3 grid((unsigned)ceil_div(p.T, tpb));
+#define MOEP_PREP_LAUNCH(EMAX)                                                                                      \
+  do {                                                                                                              \
+    if (staged)                                                                                                     \
+      hipLaunchKernelGGL((prep_kernel<EMAX, true>), grid, dim3(tpb), lds, s, logits, G, rec, p.T, p.E, p.k, p.n_act, \
+                         cap, p.rec_floats);                                                                        \
+    else                                                                                                            \
+      hipLaunchKernelGGL((prep_kernel<EMAX, false>), grid, dim3(tpb), 0, s, logits, G, rec, p.T, p.E, p.k, p.n_act,  \
+                         cap, p.rec_floats);                                                                        \
+  } while (0)
+      if (p.E <= 8) MOEP_PREP_LAUNCH(8);
+      else if (p.E <= 16) MOEP_PREP_LAUNCH(16);
+      else MOEP_PREP_LAUNCH(32);
+#undef MOEP_PREP_LAUNCH
       MOEP_HIP(hipGetLastError());
     }
     if (p.use_lut) {
