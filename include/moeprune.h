@@ -19,14 +19,15 @@
  *     stream) and the call returns without waiting for it; outputs are valid
  *     once the caller has synchronised the stream.
  *   - Only kernels are enqueued (no memset, no memcpy, no allocation), so a call can be captured
- *     into a HIP graph.  The first call that uses a GEMM kernel raises that kernel's dynamic
- *     LDS limit (hipFuncSetAttribute): make one eager call of an entry point before capturing it.
+ *     into a HIP graph.  The first call that uses a GEMM kernel or the kernel of
+ *     prune_enumerate_direct raises that kernel's dynamic LDS limit (hipFuncSetAttribute): make one
+ *     eager call of an entry point before capturing it.
  *   - Return value: a moep_status.  Nothing throws or aborts across the ABI.
  *     After a non-zero status moep_last_error() describes it.  Inputs holding
  *     NaN or Inf give unspecified results.
  *   - Same inputs give bitwise identical outputs (no floating-point atomics).
  *   - State the library keeps.  Host: the calling thread's last error message; per GPU, behind a
- *     mutex, the compute-unit count and which GEMM kernels have had their LDS limit raised (so
+ *     mutex, the compute-unit count and which kernels have had their LDS limit raised (so
  *     first calls from several host threads are safe); the event pool of moep_timing_*.  Device:
  *     512 bytes of 64-bit counters in the library's own device data, through which the persistent
  *     workgroups of the bf16 GEMM kernels line up (integer atomics on values that only grow and

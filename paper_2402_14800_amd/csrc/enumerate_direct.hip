@@ -10,6 +10,8 @@
 // coefficients of d in LDS; then the whole workgroup goes through the subsets, each thread covering its share of
 // the hidden units, a wavefront reduction per (subset, token) pair.  Pairs whose pruned routing is the full
 // routing are skipped and counted: they contribute 0 exactly.
+#include <mutex>
+
 #include "common.h"
 
 namespace moep {
@@ -198,11 +200,27 @@ __global__ __launch_bounds__(256) void direct_kernel(const float* __restrict__ l
   }
 }
 
+// The kernel's dynamic LDS limit is raised to the whole 160 KB once per instantiation and GPU (under a mutex: first
+// calls from several host threads are safe; later calls, e.g. under graph capture, only launch).
+constexpr int kMaxDevices = 64;
+std::mutex g_attr_mu;
+
 template <typename V, int EMAX, bool PREFETCH>
 int launch_direct2(const DirectPlan& p, const float* logits, const void* Y, const uint32_t* masks, int kk,
                    float* partial, uint32_t* pcnt, hipStream_t s) {
-  MOEP_HIP(hipFuncSetAttribute((const void*)direct_kernel<V, EMAX, PREFETCH>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes));
+  static bool raised[kMaxDevices] = {};
+  int dev = -1;
+  MOEP_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(MOEP_EUNSUPPORTED, "prune_enumerate_direct: device ordinal %d beyond %d", dev, kMaxDevices - 1);
+  {
+    std::lock_guard<std::mutex> lk(g_attr_mu);
+    if (!raised[dev]) {
+      MOEP_HIP(hipFuncSetAttribute((const void*)direct_kernel<V, EMAX, PREFETCH>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      raised[dev] = true;
+    }
+  }
   hipLaunchKernelGGL((direct_kernel<V, EMAX, PREFETCH>), dim3((unsigned)p.blocks), dim3(256), p.lds_bytes, s, logits,
                      (const V*)Y, masks, p.T, p.E, p.H, p.k, kk, (int)p.n_sub, partial, pcnt);
   MOEP_HIP(hipGetLastError());

@@ -938,12 +938,14 @@ def test_enumeration_and_skip_forward_replay_in_a_hip_graph():
     dt = binding.MOEP_BF16
     ws_enum = torch.empty(binding.prune_enumerate_workspace(T, E, H, k, r, dt), dtype=torch.uint8, device=DEV)
     ws_skip = torch.empty(binding.moe_forward_skip_workspace(T, E, H, F, dt), dtype=torch.uint8, device=DEV)
+    ws_dir = torch.empty(binding._lib.prune_enumerate_direct_workspace(T, E, H, k, r, dt), dtype=torch.uint8, device=DEV)
     s_logits, s_Y, s_x = logits0.clone(), Y0.clone(), d["x"].clone()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):                    # warm-up on the side stream, as torch asks before capture
         pkg.prune_enumerate(s_logits, s_Y, k, r, workspace=ws_enum)
         pkg.moe_forward_skip(s_x, *ws[1:], 0.5, workspace=ws_skip)
+        pkg.prune_enumerate_direct(s_logits, s_Y, k, r, workspace=ws_dir)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -951,6 +953,7 @@ def test_enumeration_and_skip_forward_replay_in_a_hip_graph():
         g_loss, g_amin, g_amask, g_unaff = pkg.prune_enumerate(s_logits, s_Y, k, r, workspace=ws_enum)
         g_out, g_skip, _, _ = pkg.moe_forward_skip(s_x, *ws[1:], 0.5, workspace=ws_skip,
                                                    want_logits=False, want_top2=False)
+        g_direct = pkg.prune_enumerate_direct(s_logits, s_Y, k, r, workspace=ws_dir)
     gen = torch.Generator(device=DEV)
     gen.manual_seed(99)
     for trial in range(3):
@@ -966,6 +969,10 @@ def test_enumeration_and_skip_forward_replay_in_a_hip_graph():
         assert torch.equal(g_loss.view(torch.int32), e_loss.view(torch.int32)), trial
         assert int(g_amin.item()) == int(e_amin.item()) and int(g_unaff.item()) == int(e_unaff.item())
         assert torch.equal(g_skip, e_skip) and torch.equal(g_out.view(torch.int16), e_out.view(torch.int16)), trial
+        e_direct = pkg.prune_enumerate_direct(new_logits, new_Y, k, r)
+        torch.cuda.synchronize()
+        assert torch.equal(g_direct[0].view(torch.int32), e_direct[0].view(torch.int32)), trial
+        assert torch.equal(g_direct[1], e_direct[1]) and torch.equal(g_direct[3], e_direct[3])
 
 
 # ------------------------------------------------------------------ widened entry points at full size
