@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs of this script with --copy-calibration, each
 # scaled by what the 1 GiB copy reads on the same counter: x2.000 and x1.000); the figures are in
 # profiles/hot_path_C3_hbm_traffic.txt.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"C3": 97.7e9, "C2": None, "C4": 82.7e9}   # re-measured on commit 044d00e, unchanged (C4: one launch over 16 experts)
+MEASURED_TRAFFIC_BYTES = {"C3": 97.7e9, "C2": None, "C4": 82.7e9}   # re-measured on commit 83adbb7, unchanged (C4: one launch over 16 experts)
 PEAK_ALU_LANE_OPS = 256 * 64 * 2.4e9   # CUs x lanes x clock: plain (non-packed) fp32/int lane operations per second
 PEAK_LDS_LOOKUPS = 256 * 32 * 2.4e9    # CUs x LDS banks x clock: 4-byte LDS look-ups per second without bank conflicts
 
