@@ -16,10 +16,12 @@ figures for every kernel; `cpu_baseline` times the fp64 numpy oracle on a bounde
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import math
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -55,6 +57,51 @@ def parse():
                          "rocprofv3 --pmc run of this command holds a kernel of known traffic to scale "
                          "FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
+
+
+class PowerSampler(threading.Thread):
+    """Reads the board's own telemetry (sysfs, read-only: socket power, power cap, current shader clock) every half
+    second while the timed steps run; reports nothing where the files are not there."""
+
+    def __init__(self):
+        super().__init__(daemon=True)
+        self.stop_flag = threading.Event()
+        self.power_w, self.sclk_mhz, self.cap_w, self.dev = [], [], None, None
+        for d in sorted(glob.glob("/sys/class/drm/card*/device")):
+            if glob.glob(os.path.join(d, "hwmon", "hwmon*", "power1_input")):
+                self.dev = d
+                break
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return f.read()
+        except OSError:
+            return None
+
+    def run(self):
+        if self.dev is None:
+            return
+        hw = glob.glob(os.path.join(self.dev, "hwmon", "hwmon*"))[0]
+        cap = self._read(os.path.join(hw, "power1_cap"))
+        self.cap_w = float(cap) / 1e6 if cap else None
+        while not self.stop_flag.wait(0.5):
+            p = self._read(os.path.join(hw, "power1_input"))
+            if p:
+                self.power_w.append(float(p) / 1e6)
+            for line in (self._read(os.path.join(self.dev, "pp_dpm_sclk")) or "").splitlines():
+                if line.rstrip().endswith("*"):
+                    self.sclk_mhz.append(float(line.split(":")[1].strip().rstrip("*").strip().lower().rstrip("mhz")))
+
+    def summary(self):
+        if not self.power_w:
+            return None
+        return {"socket_power_w_mean": sum(self.power_w) / len(self.power_w), "socket_power_w_max": max(self.power_w),
+                "power_cap_w": self.cap_w,
+                "shader_clock_mhz_mean": sum(self.sclk_mhz) / len(self.sclk_mhz) if self.sclk_mhz else None,
+                "shader_clock_mhz_max_of_part": 2400, "samples": len(self.power_w),
+                "source": "sysfs hwmon power1_input / power1_cap and pp_dpm_sclk, every 0.5 s during the timed steps"}
 
 
 def cpu_baseline(cfg, layer, Y, logits, torch, wl):
@@ -161,11 +208,15 @@ def main():
     pkg.kernel_timing_enable(True)
     pkg.kernel_timing_reset()
     torch.cuda.synchronize()
+    sampler = PowerSampler()
+    sampler.start()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    sampler.stop_flag.set()
+    sampler.join()
     records = pkg.kernel_timing_records()        # (kernel, ms) launch by launch, HIP events on the launch stream
     pkg.kernel_timing_enable(False)
     per_launch = {}
@@ -271,6 +322,7 @@ def main():
         "skip_fraction": 1.0 - (slots - T_skip) / T_skip if do_skip else None,
         "argmin": {str(r): int(results[r][1].item()) for r in cfg.rs},
         "roofline": roofline,
+        "power": sampler.summary(),          # the GEMMs run at the board's power cap: see the clock it leaves them
         "kernels": kernels,
     }
     # Extra leg, not part of `value`: the same forward with beta = 0 (nothing skipped), for the speedup
