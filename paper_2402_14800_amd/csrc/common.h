@@ -137,7 +137,7 @@ struct EnumPlan {
   int n_combo;       // C(n_act, kk): selections per token
   int lut_spl;       // subsets per lane of the table scorer (0 without it)
   // workspace carving (byte offsets)
-  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, off_qtab, off_sel, off_nib, total;
+  size_t off_gram, off_rec, off_masks, off_partial, off_partial_cnt, off_qtab, off_sel, off_selbits, off_nib, total;
 };
 int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p);
 // Expert outputs of the rank-limited pass: row slot_of[t, j] of Y is the output of expert

@@ -419,7 +419,9 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ re
 // Rank of the selection made by the kept-position pattern `pat` (bit j = the token's j-th ranked expert is kept):
 // the first kk set bits, as a kk-subset of the n_act positions, indexed in lexicographic order (index 0 = positions
 // 0 .. kk-1 = the selection of the full layer when kk = k).  Patterns with fewer than kk bits belong to no subset.
-__global__ __launch_bounds__(256) void selidx_kernel(int n_act, int kk, uint16_t* __restrict__ sel) {
+// selbits[i] = the positions of selection i (the pattern with exactly kk bits that has index i).
+__global__ __launch_bounds__(256) void selidx_kernel(int n_act, int kk, uint16_t* __restrict__ sel,
+                                                     uint16_t* __restrict__ selbits) {
   const uint32_t pat = blockIdx.x * 256 + threadIdx.x;
   if (pat >= (1u << n_act)) return;
   uint32_t idx = 0;
@@ -429,13 +431,15 @@ __global__ __launch_bounds__(256) void selidx_kernel(int n_act, int kk, uint16_t
     else idx += c_binom.v[n_act - 1 - j][rem - 1];     // all selections whose next position is j come first
   }
   sel[pat] = rem == 0 ? (uint16_t)idx : (uint16_t)1;     // too few bits: only idle lanes look these up (never index 0)
+  if (rem == 0 && __popc(pat) == kk) selbits[idx] = (uint16_t)pat;
 }
 
 // One workgroup per token: the error d^T G d of every selection (kk of the first n_act rank positions), the same
 // arithmetic as score_kernel's.  Selection 0 is the full layer's when kk = kfull: exactly 0.
 template <int CAP, bool EXACT>
 __global__ __launch_bounds__(256) void qtable_kernel(const float* __restrict__ rec, int kk, int kfull, int n_act_rt,
-                                                     int n_combo, float* __restrict__ qtab, int nib,
+                                                     int n_combo, const uint16_t* __restrict__ selbits,
+                                                     float* __restrict__ qtab, int nib,
                                                      uint16_t* __restrict__ nibtab) {
   constexpr int RS = rec_size(CAP);
   const int n_act = EXACT ? CAP : n_act_rt;
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(256) void qtable_kernel(const float* __restrict__ r
 #pragma unroll
   for (int j = 0; j < CAP; ++j) { ex[j] = R[j]; aw[j] = R[OFF_A + j]; }
   for (int c = threadIdx.x; c < n_combo; c += blockDim.x) {
-    const uint32_t bits = unrank_device(n_act, kk, (uint32_t)c);
+    const uint32_t bits = selbits[c];
     float w[CAP];
     float sum = 0.f;
 #pragma unroll
@@ -716,10 +720,11 @@ int plan_enumerate(int64_t T, int E, int H, int k, int r, EnumPlan* p) {
   p->off_masks = off;
   p->off_partial = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(float));
   p->off_partial_cnt = off; off += align256((size_t)p->n_tok_tiles * p->n_sub * sizeof(uint32_t));
-  p->off_qtab = p->off_sel = p->off_nib = off;
+  p->off_qtab = p->off_sel = p->off_selbits = p->off_nib = off;
   if (p->use_lut) {
     p->off_qtab = off; off += align256((size_t)T * p->n_combo * sizeof(float));
     p->off_sel = off; off += align256(((size_t)1 << p->n_act) * sizeof(uint16_t));
+    p->off_selbits = off; off += align256((size_t)p->n_combo * sizeof(uint16_t));
     p->off_nib = off; off += align256((size_t)((T + 1) / 2) * ((E + 3) / 4) * 16 * sizeof(uint32_t));
   }
   p->total = off > 0 ? off : 256;
@@ -819,18 +824,20 @@ int launch_enumerate(const EnumPlan& p, const float* logits, const void* Y, moep
       Timed t("subset_score_tables", s);
       float* qtab = (float*)(ws + p.off_qtab);
       uint16_t* sel = (uint16_t*)(ws + p.off_sel);
-      hipLaunchKernelGGL(selidx_kernel, dim3((unsigned)ceil_div((int64_t)1 << p.n_act, 256)), dim3(256), 0, s, p.n_act, p.kk, sel);
+      uint16_t* selbits = (uint16_t*)(ws + p.off_selbits);
+      hipLaunchKernelGGL(selidx_kernel, dim3((unsigned)ceil_div((int64_t)1 << p.n_act, 256)), dim3(256), 0, s, p.n_act,
+                         p.kk, sel, selbits);
       uint16_t* nibtab = (uint16_t*)(ws + p.off_nib);
       const int nib = (p.E + 3) / 4;
       const dim3 qgrid((unsigned)p.T), qblock(p.n_combo <= 64 ? 64 : 256);
 #define MOEP_QTABLE_CASE(C)                                                                                       \
   case C:                                                                                                         \
     if (p.n_act == C)                                                                                             \
-      hipLaunchKernelGGL((qtable_kernel<C, true>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo, qtab, \
-                         nib, nibtab);                                                                            \
+      hipLaunchKernelGGL((qtable_kernel<C, true>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo,       \
+                         selbits, qtab, nib, nibtab);                                                             \
     else                                                                                                          \
       hipLaunchKernelGGL((qtable_kernel<C, false>), qgrid, qblock, 0, s, rec, p.kk, p.k, p.n_act, p.n_combo,      \
-                         qtab, nib, nibtab);                                                                      \
+                         selbits, qtab, nib, nibtab);                                                             \
     break;
       switch (cap) {
         MOEP_QTABLE_CASE(2) MOEP_QTABLE_CASE(4) MOEP_QTABLE_CASE(6) MOEP_QTABLE_CASE(8) MOEP_QTABLE_CASE(12)
