@@ -240,3 +240,13 @@ def test_static_scratch_entry_point_checks_its_limit_on_the_host():
     st = binding._lib.prune_enumerate_static(p(1 << 20), p(1 << 20), 100, 8, 64, binding.MOEP_BF16, 2, 4,
                                              None, p(1 << 20), p(1 << 20), None, None)
     assert st == 1                                      # NULL loss
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Everything here runs on one GPU: bench.py --gpus N with N > 1 says so and exits before touching anything."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
